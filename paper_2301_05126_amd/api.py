@@ -1,0 +1,185 @@
+"""ctypes binding of libbnn.so -- argument marshalling only.
+
+Functions carry the names of the C entry points declared in include/bnn.h and take
+torch tensors (device memory) or raw integer addresses.  Nothing is computed here.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbnn.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2301_05126_amd.build` "
+        "(there is no fallback path)")
+
+_lib = C.CDLL(LIB_PATH)
+
+RUN_TIMED, RUN_GRAPH, RUN_STREAM = 0, 1, 2
+LAYER_CONV_FIRST_INT8, LAYER_CONV_BINARY, LAYER_FC_BINARY = 0, 1, 2
+
+
+class Epilogue(C.Structure):
+    _fields_ = [("thr", C.c_void_p), ("flip", C.c_void_p), ("pool", C.c_int)]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("kind", C.c_int), ("c_in", C.c_int), ("c_out", C.c_int),
+                ("kh", C.c_int), ("kw", C.c_int), ("pad", C.c_int), ("pad_value", C.c_int),
+                ("has_step", C.c_int), ("pool", C.c_int),
+                ("weights_dev", C.c_void_p), ("thr_dev", C.c_void_p), ("flip_dev", C.c_void_p),
+                ("preact_tap_dev", C.c_void_p), ("packed_tap_dev", C.c_void_p)]
+
+
+class LayerTiming(C.Structure):
+    _fields_ = [("gpu_us", C.c_double), ("host_us", C.c_double),
+                ("macs", C.c_int64), ("bytes_algorithmic", C.c_int64)]
+
+
+HOST_LAYER_FN = C.CFUNCTYPE(None, C.c_int, C.c_void_p)
+
+_vp, _i, _i64 = C.c_void_p, C.c_int, C.c_int64
+_lib.bnn_status_string.restype = C.c_char_p
+_lib.bnn_status_string.argtypes = [_i]
+_lib.bnn_last_hip_error.restype = _i
+_lib.bnn_version.restype = C.c_char_p
+_lib.bnn_pack_bits.argtypes = [_vp, _i64, _i64, _vp, _vp]
+_lib.bnn_conv_first_int8.argtypes = [_vp, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _i,
+                                     C.POINTER(Epilogue), _vp, _vp, _vp]
+_lib.bnn_conv_binary.argtypes = [_vp, _i, _i, _i, _i, _vp, _i, C.POINTER(Epilogue), _vp, _vp, _vp]
+_lib.bnn_fc_binary.argtypes = [_vp, _i64, _i64, _vp, _i64, C.POINTER(Epilogue), _vp, _vp, _vp]
+_lib.bnn_threshold_sign_maxpool.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp, _i, _vp, _vp]
+_lib.bnn_model_create.argtypes = [C.POINTER(LayerDesc), _i, _i, _i, _i, _i, C.POINTER(_vp)]
+_lib.bnn_model_workspace_bytes.argtypes = [_vp]
+_lib.bnn_model_workspace_bytes.restype = C.c_size_t
+_lib.bnn_model_num_layers.argtypes = [_vp]
+_lib.bnn_model_num_classes.argtypes = [_vp]
+_lib.bnn_run_model.argtypes = [_vp, _vp, _vp, _vp, C.c_size_t, _i, C.POINTER(LayerTiming),
+                               HOST_LAYER_FN, _vp, _vp]
+_lib.bnn_model_destroy.argtypes = [_vp]
+_lib.bnn_model_destroy.restype = None
+for _n in ("bnn_pack_bits", "bnn_conv_first_int8", "bnn_conv_binary", "bnn_fc_binary",
+           "bnn_threshold_sign_maxpool", "bnn_model_create", "bnn_run_model",
+           "bnn_model_num_layers", "bnn_model_num_classes"):
+    getattr(_lib, _n).restype = _i
+
+
+class BnnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        name = _lib.bnn_status_string(self.status).decode()
+        extra = f" (hipError {_lib.bnn_last_hip_error()})" if name == "BNN_ERR_HIP" else ""
+        super().__init__(f"{where}: {name}{extra}")
+
+
+def bnn_status_string(s):
+    return _lib.bnn_status_string(int(s)).decode()
+
+
+def bnn_last_hip_error():
+    return _lib.bnn_last_hip_error()
+
+
+def bnn_version():
+    return _lib.bnn_version().decode()
+
+
+def _ptr(x):
+    """Device address of a torch tensor, or a raw int / None passed through."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(st, where):
+    if st != 0:
+        raise BnnError(st, where)
+
+
+def _ep(thr, flip, pool):
+    if thr is None:
+        return None
+    return C.byref(Epilogue(_ptr(thr), _ptr(flip), int(pool)))
+
+
+def bnn_pack_bits(src, rows, k, dst, stream=None):
+    _check(_lib.bnn_pack_bits(_ptr(src), rows, k, _ptr(dst), _stream(stream)), "bnn_pack_bits")
+
+
+def bnn_conv_first_int8(inp, n, h, w, c_in, wt, c_out, kh, kw, pad, pad_value,
+                        thr=None, flip=None, pool=1, preact_out=None, packed_out=None, stream=None):
+    _check(_lib.bnn_conv_first_int8(_ptr(inp), n, h, w, c_in, _ptr(wt), c_out, kh, kw, pad, pad_value,
+                                    _ep(thr, flip, pool), _ptr(preact_out), _ptr(packed_out),
+                                    _stream(stream)), "bnn_conv_first_int8")
+
+
+def bnn_conv_binary(inp, n, h, w, c_in, wt, c_out, thr=None, flip=None, pool=1,
+                    preact_out=None, packed_out=None, stream=None):
+    _check(_lib.bnn_conv_binary(_ptr(inp), n, h, w, c_in, _ptr(wt), c_out, _ep(thr, flip, pool),
+                                _ptr(preact_out), _ptr(packed_out), _stream(stream)), "bnn_conv_binary")
+
+
+def bnn_fc_binary(a, m, k, b, n, thr=None, flip=None, c_out=None, packed_out=None, stream=None):
+    _check(_lib.bnn_fc_binary(_ptr(a), m, k, _ptr(b), n, _ep(thr, flip, 1), _ptr(c_out),
+                              _ptr(packed_out), _stream(stream)), "bnn_fc_binary")
+
+
+def bnn_threshold_sign_maxpool(preact, n, h, w, c, thr, flip, pool, packed_out, stream=None):
+    _check(_lib.bnn_threshold_sign_maxpool(_ptr(preact), n, h, w, c, _ptr(thr), _ptr(flip), pool,
+                                           _ptr(packed_out), _stream(stream)),
+           "bnn_threshold_sign_maxpool")
+
+
+class Model:
+    """Owner of a bnn_model handle (host object only)."""
+
+    def __init__(self, handle, n_layers):
+        self.handle = handle
+        self.n_layers = n_layers
+
+    def __del__(self):
+        try:
+            bnn_model_destroy(self)
+        except Exception:
+            pass
+
+
+def bnn_model_create(descs, batch, in_h, in_w, in_c):
+    arr = (LayerDesc * len(descs))(*descs)
+    out = C.c_void_p()
+    _check(_lib.bnn_model_create(arr, len(descs), batch, in_h, in_w, in_c, C.byref(out)),
+           "bnn_model_create")
+    return Model(out.value, len(descs))
+
+
+def bnn_model_workspace_bytes(model):
+    return int(_lib.bnn_model_workspace_bytes(model.handle))
+
+
+def bnn_run_model(model, input_dev, logits_dev, workspace_dev, workspace_bytes, mode=RUN_STREAM,
+                  host_fn=None, stream=None):
+    """Returns the list of LayerTiming in TIMED mode, else None."""
+    timings = (LayerTiming * model.n_layers)() if mode == RUN_TIMED else None
+    cb = HOST_LAYER_FN(lambda layer, ctx: host_fn(layer)) if host_fn else HOST_LAYER_FN(0)
+    _check(_lib.bnn_run_model(model.handle, _ptr(input_dev), _ptr(logits_dev), _ptr(workspace_dev),
+                              workspace_bytes, mode, timings, cb, None, _stream(stream)),
+           "bnn_run_model")
+    return list(timings) if timings is not None else None
+
+
+def bnn_model_destroy(model):
+    if model is not None and model.handle:
+        _lib.bnn_model_destroy(model.handle)
+        model.handle = None

@@ -1,0 +1,48 @@
+// Internal declarations shared by the translation units of libbnn (not installed).
+#ifndef BNN_INTERNAL_H
+#define BNN_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bnn.h"
+
+namespace bnn {
+
+// Where a fused step (+pool) epilogue reads its parameters and writes its results.
+// preact == nullptr: int32 pre-activations are not stored.
+// packed == nullptr: no step is applied (raw int32 output only).
+struct EpiArgs {
+    const int32_t *thr;
+    const uint8_t *flip;   // may be nullptr (no flips)
+    int32_t *preact;
+    uint32_t *packed;
+    int pool;              // 1 or 2
+};
+
+// Records a HIP error for bnn_last_hip_error() and returns BNN_ERR_HIP, or BNN_OK.
+bnn_status hip_result(hipError_t e);
+
+// Kernel launchers.  Arguments are already validated; they only pick a launch shape,
+// enqueue on `s` and report launch errors.
+bnn_status launch_pack_bits(const int8_t *src, int64_t rows, int64_t k, uint32_t *dst,
+                            hipStream_t s);
+bnn_status launch_threshold_sign_maxpool(const int32_t *x, int n, int h, int w, int c,
+                                         const int32_t *thr, const uint8_t *flip, int pool,
+                                         uint32_t *out, hipStream_t s);
+bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
+                            const EpiArgs &ep, hipStream_t s);
+bnn_status launch_conv_binary(const uint32_t *in, int n, int h, int w, int c_in,
+                              const uint32_t *wt, int c_out, const EpiArgs &ep, hipStream_t s);
+bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_in,
+                                  const int8_t *wt, int c_out, int kh, int kw, int pad,
+                                  int pad_value, const EpiArgs &ep, hipStream_t s);
+
+// Whether launch_conv_binary can run this shape (LDS budget of the input patch).
+bool conv_binary_supported(int h, int w, int c_in);
+
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace bnn
+
+#endif
