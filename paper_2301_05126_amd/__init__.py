@@ -6,6 +6,7 @@ arguments.  There is no CPU fallback: importing the package raises if the shared
 not been built (python -m paper_2301_05126_amd.build).
 """
 from . import api  # noqa: F401
+from . import runtime  # noqa: F401
 from .api import (  # noqa: F401
     BnnError, Epilogue, LayerDesc, LayerTiming, Model,
     bnn_pack_bits, bnn_conv_first_int8, bnn_conv_binary, bnn_fc_binary,
