@@ -1,14 +1,20 @@
 // Binary fully-connected layer / binary GEMM for gfx950.
 //
-// C[r][o] = K - 2 * sum_w popcount(A[r][w] ^ B[o][w])   (paper Sec. II-A neuron formula,
-// 2*popcount(xnor) - #bits, rewritten with xor so that zero tail bits contribute nothing).
+// C[r][o] = sum_t a[r][t] * b[o][t] over +-1 values stored one bit each
+//         = 2*popcount(xnor) - #bits  (paper Sec. II-A neuron formula).
 //
-// Two kernels:
-//   bgemm_tile   128x128 output tile per 256-thread block, 8x8 accumulators per lane,
-//                K streamed through LDS in 32-word chunks; inner loop is
-//                v_xor_b32 + v_bcnt_u32_b32 (the popcount instruction adds its accumulator).
-//   bgemv_rows   for m <= 8: one block per 32 outputs, each wave streams whole B rows and
-//                reduces across its 64 lanes.
+// Dense tiles run on the matrix cores: each 32-bit word of packed operand bits is expanded
+// in registers into 32 FP4 (E2M1) values +-1.0 and fed to
+// v_mfma_scale_f32_32x32x64_f8f6f4 (scales = 1.0).  Products are +-1 and partial sums are
+// integers below 2^24, so the FP32 accumulators are exact.  Both operands use the same
+// bit -> sign map (bit 1 -> -1.0) and the same permutation of K inside a word, neither of
+// which changes a dot product.  Zero-filled words beyond K (and the zero tail bits of the
+// last word) count as matches, a constant that the epilogue subtracts.
+//
+//   bgemm_mfma<TM,TN>  block = 2x2 waves, wave tile (32*TM) x (32*TN), K streamed through
+//                      LDS as packed words in 16-word chunks.
+//   bgemv_rows         m <= 8: bandwidth-bound, xor + popcount on the VALU, one wave per
+//                      output row of B, butterfly reduction over the 64 lanes.
 // Both end in the same epilogue: optional int32 store, optional threshold/flip/bit-pack.
 #include "bnn_internal.h"
 
@@ -16,14 +22,12 @@ namespace bnn {
 
 namespace {
 
-constexpr int BM = 128;      // rows of A per block
-constexpr int BN = 128;      // rows of B (outputs) per block
-constexpr int KC = 32;       // k-words per LDS chunk
-constexpr int KU = KC / 4;   // 16-byte units per LDS row
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
-// 16-byte LDS unit of (row, c4): rows are 8 units long; the unit column is xor-swizzled
-// with bits of row/8 so that the 8 (or 16) lanes that differ in row/8 hit distinct banks.
-__device__ __forceinline__ int lds_unit(int row, int c4) { return row * KU + (c4 ^ ((row >> 3) & (KU - 1))); }
+constexpr int KC = 16;        // packed k-words per LDS chunk (512 bits of K)
+constexpr int LS = KC + 4;    // LDS row stride in words; LS/4 odd -> 16-byte reads of
+                              // consecutive rows fall into distinct bank groups
 
 template <int VEC>
 __device__ __forceinline__ uint4 load_row_words(const uint32_t *__restrict__ base, int64_t row,
@@ -47,136 +51,147 @@ __device__ __forceinline__ uint4 load_row_words(const uint32_t *__restrict__ bas
     return v;
 }
 
-__device__ __forceinline__ int popc_xor4(const uint4 &a, const uint4 &b, int acc)
+// 32 packed bits -> 32 FP4 values in the low four dwords of an MFMA operand.
+// FP4 E2M1: 0b0010 = +1.0, 0b1010 = -1.0; bit b of the word lands in nibble b/4 of dword 3 - b%4.
+__device__ __forceinline__ v8i expand_fp4(uint32_t w)
 {
-    acc += __builtin_popcount(a.x ^ b.x);
-    acc += __builtin_popcount(a.y ^ b.y);
-    acc += __builtin_popcount(a.z ^ b.z);
-    acc += __builtin_popcount(a.w ^ b.w);
-    return acc;
+    v8i r;
+    r[0] = (int)(((w << 3) & 0x88888888u) | 0x22222222u);
+    r[1] = (int)(((w << 2) & 0x88888888u) | 0x22222222u);
+    r[2] = (int)(((w << 1) & 0x88888888u) | 0x22222222u);
+    r[3] = (int)((w & 0x88888888u) | 0x22222222u);
+    r[4] = 0; r[5] = 0; r[6] = 0; r[7] = 0;
+    return r;
 }
 
-// Epilogue shared by the tile kernel: lane (tx, ty) owns rows r0..r0+7 and the 8
-// contiguous outputs o0..o0+7; acc holds popcounts.  Four neighbouring lanes (tx & 3)
-// own the four bytes of one packed output word.
-__device__ __forceinline__ void tile_epilogue(const int (&acc)[8][8], int64_t r0, int64_t o0, int tx,
-                                              int64_t M, int64_t N, int K, const EpiArgs &ep)
+__device__ __forceinline__ uint32_t word_of(const uint4 &v, int q)
 {
-    if (ep.preact) {
-        const bool vec_ok = ((N & 3) == 0) && (o0 + 8 <= N);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int64_t r = r0 + i;
-            if (r >= M) continue;
-            int32_t *dst = ep.preact + r * N + o0;
-            if (vec_ok) {
-                int4 v0 = make_int4(K - 2 * acc[i][0], K - 2 * acc[i][1], K - 2 * acc[i][2], K - 2 * acc[i][3]);
-                int4 v1 = make_int4(K - 2 * acc[i][4], K - 2 * acc[i][5], K - 2 * acc[i][6], K - 2 * acc[i][7]);
-                *reinterpret_cast<int4 *>(dst) = v0;
-                *reinterpret_cast<int4 *>(dst + 4) = v1;
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (o0 + j < N) dst[j] = K - 2 * acc[i][j];
-            }
-        }
-    }
-    if (ep.packed) {
-        int thr[8];
-        unsigned flipmask = 0, valid = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const bool ok = (o0 + j) < N;
-            thr[j] = ok ? ep.thr[o0 + j] : 0;
-            if (ok) valid |= 1u << j;
-            if (ok && ep.flip && ep.flip[o0 + j]) flipmask |= 1u << j;
-        }
-        const int64_t nw = (N + 31) >> 5;
-        const int64_t word_idx = o0 >> 5;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            unsigned byte = 0;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) byte |= ((K - 2 * acc[i][j]) > thr[j] ? 1u : 0u) << j;
-            byte = (byte ^ flipmask) & valid;
-            unsigned word = byte << (8 * (tx & 3));
-            word |= __shfl_xor(word, 1);
-            word |= __shfl_xor(word, 2);
-            const int64_t r = r0 + i;
-            if ((tx & 3) == 0 && r < M && word_idx < nw) ep.packed[r * nw + word_idx] = word;
-        }
-    }
+    return q == 0 ? v.x : (q == 1 ? v.y : (q == 2 ? v.z : v.w));
 }
 
-template <int VEC>
-__global__ __launch_bounds__(256, 2) void bgemm_tile(const uint32_t *__restrict__ A,
+template <int TM, int TN, int VEC>
+__global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict__ A,
                                                       const uint32_t *__restrict__ B, int64_t M, int64_t N,
                                                       int Kw, int K, int nbn, EpiArgs ep)
 {
-    __shared__ uint4 As[BM * KU];
-    __shared__ uint4 Bs[BN * KU];
+    constexpr int BM = 64 * TM, BN = 64 * TN;     // 2 x 2 waves
+    __shared__ __align__(16) uint32_t As[BM * LS];
+    __shared__ __align__(16) uint32_t Bs[BN * LS];
 
     const int t = threadIdx.x;
-    const int tx = t & 15;
-    const int ty = t >> 4;
-    // 1-D grid: consecutive blocks walk the output tiles of one row block of A
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
     const int64_t m0 = (int64_t)(blockIdx.x / nbn) * BM;
     const int64_t n0 = (int64_t)(blockIdx.x % nbn) * BN;
 
-    int acc[8][8];
+    v16f acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = 0;
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // staging assignment: 4 units of A and 4 of B per thread per chunk
-    int srow[4], sc4[4];
+    // staging: a chunk of a tile is (rows x 4) 16-byte units; TM units of A, TN of B per thread
+    uint4 pa[TM], pb[TN];
+    auto prefetch = [&](int k0) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int idx = t + 256 * r;
-        srow[r] = idx >> 3;
-        sc4[r] = idx & 7;
-    }
-
-    uint4 pa[4], pb[4];
+        for (int r = 0; r < TM; ++r) {
+            const int idx = t + 256 * r;
+            pa[r] = load_row_words<VEC>(A, m0 + (idx >> 2), M, Kw, k0 + (idx & 3) * 4);
+        }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        pa[r] = load_row_words<VEC>(A, m0 + srow[r], M, Kw, sc4[r] * 4);
-        pb[r] = load_row_words<VEC>(B, n0 + srow[r], N, Kw, sc4[r] * 4);
-    }
+        for (int r = 0; r < TN; ++r) {
+            const int idx = t + 256 * r;
+            pb[r] = load_row_words<VEC>(B, n0 + (idx >> 2), N, Kw, k0 + (idx & 3) * 4);
+        }
+    };
+    prefetch(0);
 
     const int nchunks = (Kw + KC - 1) / KC;
+    const uint32_t *a_rd = As + (wm * TM * 32 + l32) * LS + half * 4;
+    const uint32_t *b_rd = Bs + (wn * TN * 32 + l32) * LS + half * 4;
     for (int kc = 0; kc < nchunks; ++kc) {
-        __syncthreads();   // previous chunk fully consumed
+        __syncthreads();
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            As[lds_unit(srow[r], sc4[r])] = pa[r];
-            Bs[lds_unit(srow[r], sc4[r])] = pb[r];
+        for (int r = 0; r < TM; ++r) {
+            const int idx = t + 256 * r;
+            *reinterpret_cast<uint4 *>(As + (idx >> 2) * LS + (idx & 3) * 4) = pa[r];
+        }
+#pragma unroll
+        for (int r = 0; r < TN; ++r) {
+            const int idx = t + 256 * r;
+            *reinterpret_cast<uint4 *>(Bs + (idx >> 2) * LS + (idx & 3) * 4) = pb[r];
         }
         __syncthreads();
-        if (kc + 1 < nchunks) {
-            const int k0 = (kc + 1) * KC;
+        if (kc + 1 < nchunks) prefetch((kc + 1) * KC);
+
+        // a chunk = two groups of 8 words; lane half h owns words [8g + 4h, 8g + 4h + 4)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                pa[r] = load_row_words<VEC>(A, m0 + srow[r], M, Kw, k0 + sc4[r] * 4);
-                pb[r] = load_row_words<VEC>(B, n0 + srow[r], N, Kw, k0 + sc4[r] * 4);
-            }
-        }
+        for (int g = 0; g < 2; ++g) {
+            uint4 wa[TM], wb[TN];
 #pragma unroll
-        for (int c4 = 0; c4 < KU; ++c4) {
-            uint4 a[8];
+            for (int i = 0; i < TM; ++i) wa[i] = *reinterpret_cast<const uint4 *>(a_rd + i * 32 * LS + g * 8);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) a[i] = As[lds_unit(ty * 8 + i, c4)];
+            for (int j = 0; j < TN; ++j) wb[j] = *reinterpret_cast<const uint4 *>(b_rd + j * 32 * LS + g * 8);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint4 b = Bs[lds_unit(tx * 8 + j, c4)];
+            for (int q = 0; q < 4; ++q) {
+                v8i a[TM], b[TN];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i][j] = popc_xor4(a[i], b, acc[i][j]);
+                for (int i = 0; i < TM; ++i) a[i] = expand_fp4(word_of(wa[i], q));
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[j] = expand_fp4(word_of(wb[j], q));
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            a[i], b[j], acc[i][j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
             }
         }
     }
 
-    tile_epilogue(acc, m0 + ty * 8, n0 + tx * 8, tx, M, N, K, ep);
+    // ---- epilogue.  Accumulator register r of lane (l32, half) in tile (i, j) is
+    // row 32i + 8(r/4) + 4*half + r%4, column 32j + l32.
+    const int corr = nchunks * KC * 32 - K;      // padded positions all counted as +1
+    const int64_t rbase = m0 + wm * TM * 32 + half * 4;
+    const int64_t cbase = n0 + wn * TN * 32 + l32;
+    if (ep.preact) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t col = cbase + j * 32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = rbase + i * 32 + (r >> 2) * 8 + (r & 3);
+                    if (row < M && col < N) ep.preact[row * N + col] = (int)acc[i][j][r] - corr;
+                }
+            }
+    }
+    if (ep.packed) {
+        const int64_t nw = (N + 31) >> 5;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int64_t col = cbase + j * 32;
+            const bool cok = col < N;
+            const int thr = cok ? ep.thr[col] : 0;
+            const bool flip = cok && ep.flip && ep.flip[col];
+            const int64_t wi = (n0 + wn * TN * 32 + j * 32) >> 5;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int x = (int)acc[i][j][r] - corr;
+                    const bool bit = cok && ((x > thr) != flip);
+                    const unsigned long long mask = __ballot(bit);
+                    const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
+                    const int64_t row = rbase + i * 32 + (r >> 2) * 8 + (r & 3);
+                    if (l32 == 0 && row < M && wi < nw) ep.packed[row * nw + wi] = word;
+                }
+        }
+    }
 }
 
 // m <= MT rows of A.  Block = 4 waves, 32 consecutive outputs (one packed word); wave w
@@ -237,6 +252,23 @@ __global__ __launch_bounds__(256) void bgemv_rows(const uint32_t *__restrict__ A
     }
 }
 
+template <int TM, int TN>
+bnn_status launch_mfma(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n, int kw,
+                       const EpiArgs &ep, hipStream_t s)
+{
+    const int nbn = (int)ceil_div64(n, 64 * TN);
+    const int64_t blocks = nbn * ceil_div64(m, 64 * TM);
+    if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)blocks);
+    if ((kw & 3) == 0)
+        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 4>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+    else if ((kw & 1) == 0)
+        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 2>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+    else
+        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 1>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+    return hip_result(hipGetLastError());
+}
+
 }  // namespace
 
 bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
@@ -249,15 +281,11 @@ bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint3
         hipLaunchKernelGGL(bgemv_rows<8>, grid, dim3(256), 0, s, a, b, (int)m, n, kw, (int)k, ep);
         return hip_result(hipGetLastError());
     }
-    const int nbn = (int)ceil_div64(n, BN);
-    dim3 grid((unsigned)(nbn * ceil_div64(m, BM)));
-    if ((kw & 3) == 0)
-        hipLaunchKernelGGL(bgemm_tile<4>, grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
-    else if ((kw & 1) == 0)
-        hipLaunchKernelGGL(bgemm_tile<2>, grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
-    else
-        hipLaunchKernelGGL(bgemm_tile<1>, grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
-    return hip_result(hipGetLastError());
+    // largest tile that still gives every compute unit about two blocks
+    const int64_t want = 512;
+    if (ceil_div64(m, 256) * ceil_div64(n, 256) >= want) return launch_mfma<4, 4>(a, m, k, b, n, kw, ep, s);
+    if (ceil_div64(m, 128) * ceil_div64(n, 128) >= want) return launch_mfma<2, 2>(a, m, k, b, n, kw, ep, s);
+    return launch_mfma<1, 1>(a, m, k, b, n, kw, ep, s);
 }
 
 }  // namespace bnn
