@@ -10,7 +10,10 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build", "libbnn")
 LIB = os.path.join(PKG, "libbnn.so")
 
-SOURCES = ["bnn_api.hip", "bgemm.hip", "bconv.hip", "first_layer.hip", "elementwise.hip"]
+# (source, extra defines, object name)
+UNITS = [("bnn_api.hip", [], "bnn_api.o"), ("bgemm.hip", [], "bgemm.o"), ("bconv.hip", [], "bconv.o"),
+         ("first_layer.hip", [], "first_layer.o"), ("elementwise.hip", [], "elementwise.o")]
+UNITS += [("bconv_inst.hip", [f"-DBNN_CONV_WPH={w}"], f"bconv_wph{w}.o") for w in (1, 2, 4, 8, 16)]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -21,9 +24,10 @@ FLAGS = [
 ]
 
 
-def _compile(src):
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(unit):
+    src, defines, objname = unit
+    obj = os.path.join(OBJ_DIR, objname)
+    cmd = [HIPCC] + FLAGS + defines + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
@@ -36,8 +40,8 @@ def _compile(src):
 def build(verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library.  Always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+    with ThreadPoolExecutor(max_workers=min(8, len(UNITS))) as ex:
+        objs = list(ex.map(_compile, UNITS))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

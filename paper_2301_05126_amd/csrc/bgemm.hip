@@ -53,13 +53,14 @@ __device__ __forceinline__ uint4 load_row_words(const uint32_t *__restrict__ bas
 
 // 32 packed bits -> 32 FP4 values in the low four dwords of an MFMA operand.
 // FP4 E2M1: 0b0010 = +1.0, 0b1010 = -1.0; bit b of the word lands in nibble b/4 of dword 3 - b%4.
-__device__ __forceinline__ v8i expand_fp4(uint32_t w)
+// sgn / one hold 0x88888888 / 0x22222222 in registers so that each dword is one v_and_or_b32.
+__device__ __forceinline__ v8i expand_fp4(uint32_t w, uint32_t sgn, uint32_t one)
 {
     v8i r;
-    r[0] = (int)(((w << 3) & 0x88888888u) | 0x22222222u);
-    r[1] = (int)(((w << 2) & 0x88888888u) | 0x22222222u);
-    r[2] = (int)(((w << 1) & 0x88888888u) | 0x22222222u);
-    r[3] = (int)((w & 0x88888888u) | 0x22222222u);
+    r[0] = (int)(((w << 3) & sgn) | one);
+    r[1] = (int)(((w << 2) & sgn) | one);
+    r[2] = (int)(((w << 1) & sgn) | one);
+    r[3] = (int)((w & sgn) | one);
     r[4] = 0; r[5] = 0; r[6] = 0; r[7] = 0;
     return r;
 }
@@ -109,6 +110,12 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
     };
     prefetch(0);
 
+    // VALU instructions to place behind each MFMA: 7 per expanded word, (TM+TN) words per step
+    constexpr int VPM = (7 * (TM + TN) + TM * TN - 1) / (TM * TN);
+    uint32_t sgn = 0x88888888u, one = 0x22222222u;
+    asm volatile("" : "+s"(sgn));     // keep both masks in registers (v_and_or_b32 takes no literals)
+    asm volatile("" : "+v"(one));
+
     const int nchunks = (Kw + KC - 1) / KC;
     const uint32_t *a_rd = As + (wm * TM * 32 + l32) * LS + half * 4;
     const uint32_t *b_rd = Bs + (wn * TN * 32 + l32) * LS + half * 4;
@@ -127,27 +134,42 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
         __syncthreads();
         if (kc + 1 < nchunks) prefetch((kc + 1) * KC);
 
-        // a chunk = two groups of 8 words; lane half h owns words [8g + 4h, 8g + 4h + 4)
+        // a chunk = two groups of 8 words; lane half h owns words [8g + 4h, 8g + 4h + 4).
+        // Operands of step s+1 are expanded on the VALU while the matrix core runs step s.
+        uint4 wa[2][TM], wb[2][TN];
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
-            uint4 wa[TM], wb[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) wa[i] = *reinterpret_cast<const uint4 *>(a_rd + i * 32 * LS + g * 8);
+            for (int i = 0; i < TM; ++i) wa[g][i] = *reinterpret_cast<const uint4 *>(a_rd + i * 32 * LS + g * 8);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) wb[j] = *reinterpret_cast<const uint4 *>(b_rd + j * 32 * LS + g * 8);
+            for (int j = 0; j < TN; ++j) wb[g][j] = *reinterpret_cast<const uint4 *>(b_rd + j * 32 * LS + g * 8);
+        }
+        v8i a[2][TM], b[2][TN];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                v8i a[TM], b[TN];
+        for (int i = 0; i < TM; ++i) a[0][i] = expand_fp4(wa[0][i].x, sgn, one);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) a[i] = expand_fp4(word_of(wa[i], q));
+        for (int j = 0; j < TN; ++j) b[0][j] = expand_fp4(wb[0][j].x, sgn, one);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) b[j] = expand_fp4(word_of(wb[j], q));
+        for (int st = 0; st < 8; ++st) {
+            const int cur = st & 1, nxt = cur ^ 1;
+            if (st + 1 < 8) {
+                const int g = (st + 1) >> 2, q = (st + 1) & 3;
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i) a[nxt][i] = expand_fp4(word_of(wa[g][i], q), sgn, one);
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            a[i], b[j], acc[i][j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                for (int j = 0; j < TN; ++j) b[nxt][j] = expand_fp4(word_of(wb[g][j], q), sgn, one);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        a[cur][i], b[cur][j], acc[i][j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+            // interleave: one MFMA, then its share of the next step's VALU work
+#pragma unroll
+            for (int k = 0; k < TM * TN; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
             }
         }
     }
@@ -281,8 +303,8 @@ bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint3
         hipLaunchKernelGGL(bgemv_rows<8>, grid, dim3(256), 0, s, a, b, (int)m, n, kw, (int)k, ep);
         return hip_result(hipGetLastError());
     }
-    // largest tile that still gives every compute unit about two blocks
-    const int64_t want = 512;
+    // largest tile that still fills most of the 256 compute units
+    const int64_t want = 192;
     if (ceil_div64(m, 256) * ceil_div64(n, 256) >= want) return launch_mfma<4, 4>(a, m, k, b, n, kw, ep, s);
     if (ceil_div64(m, 128) * ceil_div64(n, 128) >= want) return launch_mfma<2, 2>(a, m, k, b, n, kw, ep, s);
     return launch_mfma<1, 1>(a, m, k, b, n, kw, ep, s);
