@@ -22,6 +22,7 @@
 #ifndef BNN_BCONV_KERNEL_H
 #define BNN_BCONV_KERNEL_H
 #include "bnn_internal.h"
+#include "conv_epilogue.h"
 
 namespace bnn {
 
@@ -248,97 +249,24 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         }
     }
 
-    // ---- epilogue.  Accumulator register r of lane (l32, half) in tile (i, j) is GEMM row
-    // 32i + 8(r/4) + 4*half + r%4 = window 8i + 2(r/4) + half, sub-pixel r%4; column 32j + l32.
-    const int corr = 9 * CWP * 32 - g.k_bits;          // padded positions all counted as +1
-    const int cbase = o_blk + wn * TN * 32 + l32;
-    const int lhw = g.ltw - 1, lhh = g.lth - 1;
-    if (ep.preact) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int a4 = 0; a4 < 4; ++a4) {
-                const int wq = (wm * TM * 32 + i * 32) / 4 + 2 * a4 + half;
-                const int wx = wq & ((1 << lhw) - 1);
-                const int wy = (wq >> lhw) & ((1 << lhh) - 1);
-                const int img = img0 + (wq >> (lhw + lhh));
-#pragma unroll
-                for (int sub = 0; sub < 4; ++sub) {
-                    const int y = y0 + 2 * wy + (sub >> 1), x = x0 + 2 * wx + (sub & 1);
-                    if (img < g.n && y < g.h && x < g.w) {
-                        int32_t *dst = ep.preact + (((int64_t)img * g.h + y) * g.w + x) * g.c_out;
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            const int col = cbase + j * 32;
-                            if (col < g.c_out) dst[col] = (int)acc[i][j][a4 * 4 + sub] - corr;
-                        }
-                    }
-                }
-            }
-    }
+    // ---- epilogue (shared with the first layer): sums minus the padded positions, which all
+    // counted as +1
+    const int corr = 9 * CWP * 32 - g.k_bits;
+    TilePos pos;
+    pos.n = g.n; pos.h = g.h; pos.w = g.w; pos.c_out = g.c_out;
+    pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = img0; pos.y0 = y0; pos.x0 = x0;
+    auto getx = [&](int i, int j, int r) { return (int)acc[i][j][r] - corr; };
+    if (ep.preact) conv_tile_store_preact<TM, TN>(getx, wm * TM * 32, o_blk + wn * TN * 32, l32, half, pos, ep.preact);
     if (ep.packed) {
-        const int cwo = (g.c_out + 31) >> 5;
-        const int ho = g.h >> 1, wo = g.w >> 1;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = cbase + j * 32;
-            const bool cok = col < g.c_out;
-            const int thr = cok ? ep.thr[col] : 0;
-            const bool flip = cok && ep.flip && ep.flip[col];
-            const int wi = (o_blk + wn * TN * 32 + j * 32) >> 5;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    const int wq = (wm * TM * 32 + i * 32) / 4 + 2 * a4 + half;
-                    const int wx = wq & ((1 << lhw) - 1);
-                    const int wy = (wq >> lhw) & ((1 << lhh) - 1);
-                    const int img = img0 + (wq >> (lhw + lhh));
-                    bool bits[4];
-#pragma unroll
-                    for (int sub = 0; sub < 4; ++sub) {
-                        const int x = (int)acc[i][j][a4 * 4 + sub] - corr;
-                        bits[sub] = cok && ((x > thr) != flip);
-                    }
-                    if (ep.pool == 2) {
-                        const bool bit = bits[0] || bits[1] || bits[2] || bits[3];
-                        const unsigned long long mask = __ballot(bit);
-                        const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
-                        const int yo = (y0 >> 1) + wy, xo = (x0 >> 1) + wx;
-                        if (l32 == 0 && img < g.n && yo < ho && xo < wo && wi < cwo)
-                            ep.packed[(((int64_t)img * ho + yo) * wo + xo) * cwo + wi] = word;
-                    } else {
-#pragma unroll
-                        for (int sub = 0; sub < 4; ++sub) {
-                            const unsigned long long mask = __ballot(bits[sub]);
-                            const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
-                            const int y = y0 + 2 * wy + (sub >> 1), x = x0 + 2 * wx + (sub & 1);
-                            if (l32 == 0 && img < g.n && y < g.h && x < g.w && wi < cwo)
-                                ep.packed[(((int64_t)img * g.h + y) * g.w + x) * cwo + wi] = word;
-                        }
-                    }
-                }
-        }
+        // bits -> LDS tile [output pixel][2*TN words] (reusing the weight buffer) -> coalesced stores
+        constexpr int BW = 2 * TN;
+        __syncthreads();                      // every wave is done with the weight chunk
+        conv_tile_step_to_lds<TM, TN>(getx, wm * TM * 32, o_blk + wn * TN * 32, wn * TN, BW, l32, half, pos, ep, Bs);
+        __syncthreads();
+        conv_tile_copy_out<BW>(Bs, 64 * TM, o_blk >> 5, pos, ep, t);
     }
 }
 
-int log2_ceil(int v)
-{
-    int l = 0;
-    while ((1 << l) < v) ++l;
-    return l;
-}
-
-// words per lane half per tap for a layer of cw words per pixel (cw <= 32)
-int wph_for(int cw)
-{
-    int wph = 1;
-    while (2 * wph < cw) wph *= 2;
-    return wph;
-}
-
-// Spatial tile for `pixels` = 64*TM pixels per block: as wide as the image allows (<= 16),
-// then as tall as allowed, the rest filled with further images.
 ConvGeom make_geom(int n, int h, int w, int c_in, int c_out, int pixels, int bn)
 {
     ConvGeom g;
@@ -346,16 +274,9 @@ ConvGeom make_geom(int n, int h, int w, int c_in, int c_out, int pixels, int bn)
     g.cw = (c_in + 31) / 32;
     g.c_out = c_out;
     g.k_bits = 9 * c_in;
-    const int lp = log2_ceil(pixels);
-    int ltw = log2_ceil(w);
-    ltw = ltw < 1 ? 1 : (ltw > 4 ? 4 : ltw);
-    int lth = log2_ceil(h);
-    lth = lth < 1 ? 1 : lth;
-    if (lth > lp - ltw) lth = lp - ltw;
-    g.ltw = ltw; g.lth = lth;
-    g.ni = pixels >> (ltw + lth);
-    g.tiles_x = (w + (1 << ltw) - 1) >> ltw;
-    g.tiles_y = (h + (1 << lth) - 1) >> lth;
+    const TileShape ts = make_tile_shape(h, w, pixels);
+    g.ltw = ts.ltw; g.lth = ts.lth; g.ni = ts.ni;
+    g.tiles_x = ts.tiles_x; g.tiles_y = ts.tiles_y;
     g.n_co_tiles = (c_out + bn - 1) / bn;
     return g;
 }

@@ -4,13 +4,25 @@
 // (paper Sec. II-A convolutional layer applied to the 8-bit input image; with
 // kh = kw = h = w = 1 it is the fully-connected first layer of an MLP).
 //
-// One lane = one output pixel x 32 output channels.  The flattened taps (i, j, c) are taken
+// Three kernels, picked by shape:
+//   conv_first_mfma   small kernels (kh * roundup16(kw*c_in) <= 128 bytes per pixel): the int8
+//                     input patch and the block's weights live in LDS; each lane gathers 16
+//                     contiguous patch bytes (one kernel row of one pixel) per MFMA operand
+//                     and v_mfma_i32_32x32x32_i8 does the sums.  Pixels are window-major, the
+//                     epilogue is the one of the binary convolution.
+//   fc_first_mfma     1x1 kernels without padding and c_in % 16 == 0 (the MLP's first layer):
+//                     an int8 GEMM whose operands are read straight from global memory.
+//   conv_first_kernel any other shape: one lane = one output pixel x 32 output channels with
+//                     v_dot4_i32_i8.
+//
+// conv_first_kernel: one lane = one output pixel x 32 output channels.  The flattened taps (i, j, c) are taken
 // four at a time with v_dot4_i32_i8: the lane gathers its four activation bytes into a
 // dword, the block keeps the weights of its 32 channels in LDS as [tap group][channel]
 // dwords (zero beyond K), so every lane of a wave reads the same LDS address (broadcast).
 // With pool == 2 lanes are ordered window-major: four neighbouring lanes hold the 2x2
 // window and OR their bit words.
 #include "bnn_internal.h"
+#include "conv_epilogue.h"
 
 namespace bnn {
 
@@ -121,6 +133,265 @@ __global__ __launch_bounds__(256) void conv_first_kernel(const int8_t *__restric
     }
 }
 
+// ------------------------------------------------------------------ matrix-core kernels
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct FirstGeomM {
+    int n, h, w, c_in, c_out, kh, kw, pad, pad_value;
+    int ho, wo;
+    int lth, ltw, ni, tiles_x, tiles_y, n_co_tiles, n_items;
+    int sl, slp, kp;            // bytes of one kernel row, padded to 16, and padded K (multiple of 32)
+    int patch_bytes;
+};
+
+// Block = 4 waves x 64 pixels (two 32-row tiles each) x NG groups of 64 channels, taken one
+// group after the other; blocks are persistent (weights staged once, then a grid-stride
+// walk over the pixel tiles).  Output bits go through an LDS tile and leave as one vector
+// store per pixel.
+// K is ordered [kernel row ti][tj*c_in + c], every kernel row zero-padded to slp bytes on
+// the weight side; the activation bytes behind a short row are whatever follows in the
+// patch and meet zero weights.
+template <int NG>
+__global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restrict__ in,
+                                                       const int8_t *__restrict__ wt, FirstGeomM g, EpiArgs ep)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int ws = g.kp + 16;                                   // weight row stride in bytes
+    constexpr int TN = 2;                                       // 32-channel tiles per group
+    constexpr int BW = 2 * NG;                                  // packed output words per pixel
+    unsigned char *Wl = smem;                                   // [64*NG][ws]
+    uint32_t *Ol = reinterpret_cast<uint32_t *>(smem + 64 * NG * ws);      // [256][BW]
+    unsigned char *Pl = smem + 64 * NG * ws + 256 * BW * 4;     // [ni][ph][pw][c_in] + slack
+
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const int co_tile = blockIdx.y;
+    const int th = 1 << g.lth, tw = 1 << g.ltw;
+    const int o_blk = co_tile * 64 * NG;
+    const int pw = tw + g.kw - 1, ph = th + g.kh - 1;
+
+    // ---- weights of this block's channels in the K-padded layout, staged once per block:
+    // zero the tile, then scatter the source bytes (independent loads, several in flight)
+    {
+        const int k_total = g.kh * g.sl;
+        const int nrow = 64 * NG;
+        for (int idx = t; idx < nrow * (ws >> 2); idx += 256) reinterpret_cast<unsigned *>(Wl)[idx] = 0u;
+        __syncthreads();
+        const int rows_here = min(nrow, g.c_out - o_blk);
+        const int total = rows_here * k_total;
+        const int8_t *wsrc = wt + (int64_t)o_blk * k_total;       // rows are contiguous in memory
+        for (int base = 0; base < total; base += 256 * 8) {
+            int8_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256 + t;
+                v[u] = idx < total ? wsrc[idx] : (int8_t)0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256 + t;
+                if (idx < total) {
+                    const int row = idx / k_total, kk = idx - row * k_total;
+                    const int ti = kk / g.sl, off = kk - ti * g.sl;
+                    Wl[row * ws + ti * g.slp + off] = (unsigned char)v[u];
+                }
+            }
+        }
+    }
+
+    // ---- this lane's two pixels (window-major rows of the implicit GEMM)
+    int pixbyte[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int p = wave * 64 + i * 32 + l32;
+        const int wq = p >> 2, sub = p & 3;
+        const int wx = wq & ((tw >> 1) - 1);
+        const int wy = (wq >> (g.ltw - 1)) & ((th >> 1) - 1);
+        const int il = wq >> (g.ltw - 1 + g.lth - 1);
+        const int py = 2 * wy + (sub >> 1), px = 2 * wx + (sub & 1);
+        pixbyte[i] = ((il * ph + py) * pw + px) * g.c_in;
+    }
+    const int u16 = g.slp >> 4;                  // 16-byte units per kernel row
+    const int nsteps = g.kp >> 5;
+    const unsigned *P32 = reinterpret_cast<const unsigned *>(Pl);
+
+    // ---- persistent loop over (image group, tile) work items
+    for (int item = blockIdx.x; item < g.n_items; item += gridDim.x) {
+        int rest = item;
+        const int tile_x = rest % g.tiles_x; rest /= g.tiles_x;
+        const int tile_y = rest % g.tiles_y; rest /= g.tiles_y;
+        const int img0 = rest * g.ni;
+        const int y0 = tile_y * th, x0 = tile_x * tw;
+
+        __syncthreads();          // previous item's patch fully consumed (and weights staged)
+        // input patch as bytes, pad_value outside the image; the slack behind it is zeroed.
+        // Loads of four bytes per thread are issued together, then stored.
+        {
+#ifdef BNN_X_NOPATCH
+            const int total = 0;
+#else
+            const int total = g.ni * ph * pw * g.c_in;
+#endif
+            for (int base = 0; base < g.patch_bytes; base += 256 * 4) {
+                int v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = base + u * 256 + t;
+                    v[u] = 0;
+                    if (idx < total) {
+                        const int c = idx % g.c_in;
+                        int p = idx / g.c_in;
+                        const int px = p % pw; p /= pw;
+                        const int py = p % ph;
+                        const int il = p / ph;
+                        const int y = y0 + py - g.pad, x = x0 + px - g.pad, img = img0 + il;
+                        v[u] = g.pad_value;
+                        if (img < g.n && y >= 0 && y < g.h && x >= 0 && x < g.w)
+                            v[u] = in[(((int64_t)img * g.h + y) * g.w + x) * g.c_in + c];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = base + u * 256 + t;
+                    if (idx < g.patch_bytes) Pl[idx] = (unsigned char)(int8_t)v[u];
+                }
+            }
+        }
+        __syncthreads();
+
+        TilePos pos;
+        pos.n = g.n; pos.h = g.ho; pos.w = g.wo; pos.c_out = g.c_out;
+        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = img0; pos.y0 = y0; pos.x0 = x0;
+
+        // activation operands of all K steps (at most 4), gathered once per tile
+        v4i a[4][2];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks >= nsteps) break;
+            const int k16 = 2 * ks + half;
+            const int ti = k16 / u16, off = (k16 - ti * u16) << 4;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                // 16 bytes from an arbitrary byte address: five aligned dwords, funnel-shifted
+                const int addr = ti < g.kh ? pixbyte[i] + ti * pw * g.c_in + off : 0;
+                const int d = addr >> 2;
+                const unsigned sh = (unsigned)addr & 3u;
+                const unsigned w0 = P32[d], w1 = P32[d + 1], w2 = P32[d + 2], w3 = P32[d + 3], w4 = P32[d + 4];
+                a[ks][i][0] = (int)__builtin_amdgcn_alignbyte(w1, w0, sh);
+                a[ks][i][1] = (int)__builtin_amdgcn_alignbyte(w2, w1, sh);
+                a[ks][i][2] = (int)__builtin_amdgcn_alignbyte(w3, w2, sh);
+                a[ks][i][3] = (int)__builtin_amdgcn_alignbyte(w4, w3, sh);
+            }
+        }
+
+#pragma unroll 1
+        for (int grp = 0; grp < NG; ++grp) {
+            v16i acc[2][TN];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks >= nsteps) break;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const v4i b = *reinterpret_cast<const v4i *>(Wl + ((grp * TN + j) * 32 + l32) * ws + ks * 32 + half * 16);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks][i], b, acc[i][j], 0, 0, 0);
+                }
+            }
+            auto getx = [&](int i, int j, int r) { return acc[i][j][r]; };
+            const int ch0 = o_blk + grp * 64;
+            if (ep.preact) conv_tile_store_preact<2, TN>(getx, wave * 64, ch0, l32, half, pos, ep.preact);
+#ifndef BNN_X_NOEPI
+            if (ep.packed) conv_tile_step_to_lds<2, TN>(getx, wave * 64, ch0, grp * TN, BW, l32, half, pos, ep, Ol);
+#else
+            if (acc[0][0][0] == 0x12345678 && acc[1][1][5] == 77) ep.packed[0] = 1;
+#endif
+        }
+#ifndef BNN_X_NOEPI
+        if (ep.packed) {
+            __syncthreads();
+            conv_tile_copy_out<BW>(Ol, 256, o_blk >> 5, pos, ep, t);
+        }
+#endif
+    }
+}
+
+// 1x1, pad 0, c_in % 16 == 0: int8 GEMM  X[m][o] = sum_c A[m][c] * W[o][c];  m = pixel index.
+// Block = 2 x 2 waves, one 32 x 32 tile each; operands are 16-byte global loads.
+__global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ A, const int8_t *__restrict__ Wt,
+                                                     int64_t M, int N, int K, EpiArgs ep)
+{
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int nbn = (N + 63) / 64;
+    const int64_t m0 = (int64_t)(blockIdx.x / nbn) * 64 + (wave >> 1) * 32;
+    const int n0 = (blockIdx.x % nbn) * 64 + (wave & 1) * 32;
+    const int64_t arow = (m0 + l32 < M) ? m0 + l32 : M - 1;
+    const int brow = (n0 + l32 < N) ? n0 + l32 : N - 1;
+    const int8_t *ap = A + arow * K + half * 16;
+    const int8_t *bp = Wt + (int64_t)brow * K + half * 16;
+    v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
+    const int nsteps = (K + 31) / 32;
+#pragma unroll 4
+    for (int ks = 0; ks < nsteps; ++ks) {
+        const bool ok = ks * 32 + half * 16 < K;         // K % 16 == 0: a 16-byte slice is all in or all out
+        const int koff = ok ? ks * 32 : 0;
+        v4i a = *reinterpret_cast<const v4i *>(ap + koff);
+        v4i b = *reinterpret_cast<const v4i *>(bp + koff);
+        if (!ok) { a = v4i{0, 0, 0, 0}; b = v4i{0, 0, 0, 0}; }
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc, 0, 0, 0);
+    }
+    const int col = n0 + l32;
+    const bool cok = col < N;
+    if (ep.preact) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (row < M && cok) ep.preact[row * N + col] = acc[r];
+        }
+    }
+    if (ep.packed) {
+        const int nw = (N + 31) >> 5;
+        const int thr = cok ? ep.thr[col] : 0;
+        const bool flip = cok && ep.flip && ep.flip[col];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool bit = cok && ((acc[r] > thr) != flip);
+            const unsigned long long mask = __ballot(bit);
+            const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
+            const int64_t row = m0 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (l32 == 0 && row < M && (n0 >> 5) < nw) ep.packed[row * nw + (n0 >> 5)] = word;
+        }
+    }
+}
+
+template <int NG>
+bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, const EpiArgs &ep, hipStream_t s)
+{
+    g.n_co_tiles = (g.c_out + 64 * NG - 1) / (64 * NG);
+    const size_t smem = (size_t)64 * NG * (g.kp + 16) + 256 * 2 * NG * 4 + g.patch_bytes;
+    const int64_t items = (int64_t)g.tiles_x * g.tiles_y * ((g.n + g.ni - 1) / g.ni);
+    if (smem > 64 * 1024 || items > 0x7fffffffLL || g.n_co_tiles > 65535) return BNN_ERR_UNSUPPORTED;
+    g.n_items = (int)items;
+    // persistent blocks: weights are staged once, then the block walks its share of the tiles
+    const int64_t cap = 256 * 2;
+    const unsigned bx = (unsigned)(items < cap ? items : cap);
+    hipLaunchKernelGGL(conv_first_mfma<NG>, dim3(bx, (unsigned)g.n_co_tiles), dim3(256), smem, s, in, wt, g, ep);
+    return hip_result(hipGetLastError());
+}
+
 }  // namespace
 
 bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_in, const int8_t *wt,
@@ -128,6 +399,36 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
                                   hipStream_t s)
 {
     if (n == 0) return BNN_OK;
+    const int ho_ = h + 2 * pad - kh + 1, wo_ = w + 2 * pad - kw + 1;
+    const int pool_ = ep.packed ? ep.pool : 1;
+    // int8 GEMM straight from global memory
+    if (kh == 1 && kw == 1 && pad == 0 && (c_in & 15) == 0 && pool_ == 1) {
+        const int64_t M = (int64_t)n * h * w;
+        const int64_t blocks = ceil_div64(M, 64) * ceil_div64(c_out, 64);
+        if (blocks <= 0x7fffffffLL) {
+            hipLaunchKernelGGL(fc_first_mfma, dim3((unsigned)blocks), dim3(256), 0, s, in, wt, M, c_out, c_in, ep);
+            return hip_result(hipGetLastError());
+        }
+    }
+    // small kernels: patch + weights in LDS, matrix cores
+    {
+        FirstGeomM g;
+        g.n = n; g.h = h; g.w = w; g.c_in = c_in; g.c_out = c_out;
+        g.kh = kh; g.kw = kw; g.pad = pad; g.pad_value = pad_value;
+        g.ho = ho_; g.wo = wo_;
+        g.sl = kw * c_in;
+        g.slp = (g.sl + 15) & ~15;
+        g.kp = (kh * g.slp + 31) & ~31;
+        const TileShape ts = make_tile_shape(ho_, wo_, 256);
+        g.lth = ts.lth; g.ltw = ts.ltw; g.ni = ts.ni; g.tiles_x = ts.tiles_x; g.tiles_y = ts.tiles_y;
+        const int64_t pbytes = (int64_t)g.ni * ((1 << g.lth) + kh - 1) * ((1 << g.ltw) + kw - 1) * c_in;
+        g.patch_bytes = (int)((pbytes + 32 + 15) & ~15LL);       // slack: reads run past short rows
+        if (g.kp <= 128 && pbytes <= 24 * 1024) {
+            const bnn_status st = (c_out > 64) ? launch_first_mfma<2>(in, wt, g, ep, s)
+                                               : launch_first_mfma<1>(in, wt, g, ep, s);
+            if (st != BNN_ERR_UNSUPPORTED) return st;
+        }
+    }
     FirstGeom g;
     g.n = n; g.h = h; g.w = w; g.c_in = c_in; g.c_out = c_out;
     g.kh = kh; g.kw = kw; g.pad = pad; g.pad_value = pad_value;
