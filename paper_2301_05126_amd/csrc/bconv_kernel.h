@@ -261,7 +261,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         // bits -> LDS tile [output pixel][2*TN words] (reusing the weight buffer) -> coalesced stores
         constexpr int BW = 2 * TN;
         __syncthreads();                      // every wave is done with the weight chunk
-        conv_tile_step_to_lds<TM, TN>(getx, wm * TM * 32, o_blk + wn * TN * 32, wn * TN, BW, l32, half, pos, ep, Bs);
+        const StepCols<TN> sc = load_step_cols<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
+        conv_tile_step_to_lds<TM, TN>(getx, wm * TM * 32, wn * TN, BW, lane, sc, ep.pool, Bs);
         __syncthreads();
         conv_tile_copy_out<BW>(Bs, 64 * TM, o_blk >> 5, pos, ep, t);
     }

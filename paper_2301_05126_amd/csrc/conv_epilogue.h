@@ -10,6 +10,8 @@
 #ifndef BNN_CONV_EPILOGUE_H
 #define BNN_CONV_EPILOGUE_H
 
+#include <utility>
+
 #include "bnn_internal.h"
 
 namespace bnn {
@@ -52,43 +54,100 @@ __device__ __forceinline__ void conv_tile_store_preact(GetX getx, int row0, int 
         }
 }
 
+// v_writelane_b32: put a wave-uniform value into lane `LANE` of a register.
+template <int LANE>
+__device__ __forceinline__ int write_lane(int old, unsigned value)
+{
+    const unsigned uniform = __builtin_amdgcn_readfirstlane(value);   // pins the value to a scalar register
+    asm("v_writelane_b32 %0, %1, %2" : "+v"(old) : "s"(uniform), "n"(LANE));
+    return old;
+}
+
+// Per-column step parameters of one wave: the threshold of this lane's channel in each of
+// its TN tiles, and wave-wide masks (bit = lane) of the lanes whose channel is flipped /
+// exists.  Loaded once per block.
+template <int TN>
+struct StepCols {
+    int thr[TN];
+    unsigned long long flipmask[TN], okmask[TN];
+};
+
+template <int TN>
+__device__ __forceinline__ StepCols<TN> load_step_cols(const EpiArgs &ep, int ch0, int l32, int c_out)
+{
+    StepCols<TN> sc;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = ch0 + j * 32 + l32;
+        const bool cok = col < c_out;
+        sc.thr[j] = cok ? ep.thr[col] : 0;
+        sc.flipmask[j] = __ballot(cok && ep.flip && ep.flip[col]);
+        sc.okmask[j] = __ballot(cok);
+    }
+    return sc;
+}
+
 // Step (+ pool) of one wave's tiles into the block's LDS output tile.
 // out_lds is [output pixel of the block][bw words]; an output pixel is a GEMM row (pool 1)
 // or a window (pool 2); word0 = index, inside the block's bw words, of this wave's first
-// 32 channels.  Channels beyond c_out give zero bits.
-template <int TM, int TN, typename GetX>
-__device__ __forceinline__ void conv_tile_step_to_lds(GetX getx, int row0, int ch0, int word0, int bw,
-                                                      int l32, int half, const TilePos &p, const EpiArgs &ep,
-                                                      uint32_t *out_lds)
+// 32 channels.  A compare writes a 64-lane mask whose halves are the packed words of two
+// rows; the words are parked in lanes of a register (v_writelane) and leave with one LDS
+// store per 64 words.  Channels beyond c_out give zero bits.
+// One parked word pair: mask halves -> lanes K and 32 + K of `parked`.
+template <int K>
+__device__ __forceinline__ int park_pair(int parked, unsigned long long m)
 {
-    const int col0 = ch0 + l32;
+    parked = write_lane<K>(parked, (unsigned)m);
+    parked = write_lane<32 + K>(parked, (unsigned)(m >> 32));
+    return parked;
+}
+
+template <int TM, int TN, typename GetX, int... R>
+__device__ __forceinline__ int park_rows(GetX getx, int i, int j, int thr, unsigned long long fm,
+                                         unsigned long long om, std::integer_sequence<int, R...>)
+{
+    int parked = 0;
+    ((parked = park_pair<R>(parked, (__ballot(getx(i, j, R) > thr) ^ fm) & om)), ...);
+    return parked;
+}
+
+template <int TM, int TN, typename GetX, int... W>
+__device__ __forceinline__ int park_windows(GetX getx, int j, int thr, unsigned long long fm,
+                                            unsigned long long om, std::integer_sequence<int, W...>)
+{
+    int parked = 0;
+    auto window = [&](int i, int a4) {
+        unsigned long long m = 0;
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) m |= __ballot(getx(i, j, a4 * 4 + sub) > thr) ^ fm;
+        return m & om;
+    };
+    ((parked = park_pair<W>(parked, window(W / 4, W % 4))), ...);
+    return parked;
+}
+
+template <int TM, int TN, typename GetX>
+__device__ __forceinline__ void conv_tile_step_to_lds(GetX getx, int row0, int word0, int bw, int lane,
+                                                      const StepCols<TN> &sc, int pool, uint32_t *out_lds)
+{
+    const int k = lane & 31, hf = lane >> 5;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int col = col0 + j * 32;
-        const bool cok = col < p.c_out;
-        const int thr = cok ? ep.thr[col] : 0;
-        const bool flip = cok && ep.flip && ep.flip[col];
+        const unsigned long long fm = sc.flipmask[j], om = sc.okmask[j];
+        const int thr = sc.thr[j];
+        if (pool == 2) {
+            // window W = 4i + a4 of this wave -> lanes W (lower rows) and 32 + W
+            const int parked = park_windows<TM, TN>(getx, j, thr, fm, om, std::make_integer_sequence<int, TM * 4>{});
+            // lane (k, hf) holds window (row0/4) + 8*(k/4) + 2*(k%4) + hf
+            if (k < TM * 4) out_lds[((row0 >> 2) + (k >> 2) * 8 + (k & 3) * 2 + hf) * bw + word0 + j] = (uint32_t)parked;
+        } else {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int a4 = 0; a4 < 4; ++a4) {
-                const int wq = (row0 + i * 32) / 4 + 2 * a4 + half;
-                bool bits[4];
-#pragma unroll
-                for (int sub = 0; sub < 4; ++sub) bits[sub] = cok && ((getx(i, j, a4 * 4 + sub) > thr) != flip);
-                if (ep.pool == 2) {
-                    const unsigned long long mask = __ballot(bits[0] || bits[1] || bits[2] || bits[3]);
-                    const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
-                    if (l32 == 0) out_lds[wq * bw + word0 + j] = word;
-                } else {
-#pragma unroll
-                    for (int sub = 0; sub < 4; ++sub) {
-                        const unsigned long long mask = __ballot(bits[sub]);
-                        const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
-                        if (l32 == 0) out_lds[(wq * 4 + sub) * bw + word0 + j] = word;
-                    }
-                }
+            for (int i = 0; i < TM; ++i) {
+                const int parked = park_rows<TM, TN>(getx, i, j, thr, fm, om, std::make_integer_sequence<int, 16>{});
+                // lane (k, hf), k < 16, holds row row0 + 32i + 8*(k/4) + 4*hf + k%4
+                if (k < 16) out_lds[(row0 + i * 32 + (k >> 2) * 8 + hf * 4 + (k & 3)) * bw + word0 + j] = (uint32_t)parked;
             }
+        }
     }
 }
 

@@ -218,6 +218,13 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
     const int nsteps = g.kp >> 5;
     const unsigned *P32 = reinterpret_cast<const unsigned *>(Pl);
 
+    // per-channel step parameters, loaded once per block
+    StepCols<TN> sc[NG];
+    if (ep.packed) {
+#pragma unroll
+        for (int grp = 0; grp < NG; ++grp) sc[grp] = load_step_cols<TN>(ep, o_blk + grp * 64, l32, g.c_out);
+    }
+
     // ---- persistent loop over (image group, tile) work items
     for (int item = blockIdx.x; item < g.n_items; item += gridDim.x) {
         int rest = item;
@@ -311,7 +318,7 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
             const int ch0 = o_blk + grp * 64;
             if (ep.preact) conv_tile_store_preact<2, TN>(getx, wave * 64, ch0, l32, half, pos, ep.preact);
 #ifndef BNN_X_NOEPI
-            if (ep.packed) conv_tile_step_to_lds<2, TN>(getx, wave * 64, ch0, grp * TN, BW, l32, half, pos, ep, Ol);
+            if (ep.packed) conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, lane, sc[grp], ep.pool, Ol);
 #else
             if (acc[0][0][0] == 0x12345678 && acc[1][1][5] == 77) ep.packed[0] = 1;
 #endif
