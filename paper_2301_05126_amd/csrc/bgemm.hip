@@ -13,8 +13,8 @@
 //
 //   bgemm_mfma<TM,TN>  block = 2x2 waves, wave tile (32*TM) x (32*TN), K streamed through
 //                      LDS as packed words in 16-word chunks.
-//   bgemv_rows         m <= 8: bandwidth-bound, xor + popcount on the VALU, one wave per
-//                      output row of B, butterfly reduction over the 64 lanes.
+//   bgemv_rows         m <= 8: bandwidth-bound, xor + popcount on the VALU, four output rows of
+//                      B per wave, halving-butterfly reduction over the 64 lanes.
 // Both end in the same epilogue: optional int32 store, optional threshold/flip/bit-pack.
 #include "bnn_internal.h"
 
@@ -216,11 +216,13 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
     }
 }
 
-// m <= MT rows of A.  Block = 4 waves, 32 consecutive outputs (one packed word); wave w
-// takes outputs 8w..8w+7 one after another, lanes stride the K words, then a butterfly
-// reduction over the 64 lanes.
-template <int MT>
-__global__ __launch_bounds__(256) void bgemv_rows(const uint32_t *__restrict__ A,
+// m <= MT rows of A (batch 1 .. 8): bandwidth / latency bound, on the VALU.
+// Block = 8 waves = 32 consecutive outputs (one packed word); wave w owns outputs 4w..4w+3
+// and streams their B rows with all loads of a K slice in flight at once.  Lanes stride K
+// (16 bytes per lane when VEC == 4), accumulate popcount(a ^ b), then a halving butterfly
+// reduces the 4 partial sums per lane over the 64 lanes with 2 + 1 + 4 shuffles per row.
+template <int MT, int VEC>
+__global__ __launch_bounds__(512) void bgemv_rows(const uint32_t *__restrict__ A,
                                                   const uint32_t *__restrict__ B, int M, int64_t N, int Kw,
                                                   int K, EpiArgs ep)
 {
@@ -229,48 +231,87 @@ __global__ __launch_bounds__(256) void bgemv_rows(const uint32_t *__restrict__ A
     const int wave = threadIdx.x >> 6;
     const int64_t o_base = (int64_t)blockIdx.x * 32;
 
-    for (int q = 0; q < 8; ++q) {
-        const int ol = wave * 8 + q;
-        const int64_t o = o_base + ol;
-        int acc[MT];
+    int acc[MT][4];
 #pragma unroll
-        for (int r = 0; r < MT; ++r) acc[r] = 0;
-        if (o < N) {
-            const uint32_t *brow = B + o * (int64_t)Kw;
-            for (int w = lane; w < Kw; w += 64) {
-                const uint32_t b = brow[w];
+    for (int r = 0; r < MT; ++r)
 #pragma unroll
-                for (int r = 0; r < MT; ++r)
-                    if (r < M) acc[r] += __builtin_popcount(A[(int64_t)r * Kw + w] ^ b);
+        for (int q = 0; q < 4; ++q) acc[r][q] = 0;
+
+    const uint32_t *brow[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t o = o_base + wave * 4 + q;
+        brow[q] = B + (o < N ? o : N - 1) * (int64_t)Kw;      // rows past N are computed, never stored
+    }
+    if (VEC == 4) {
+        for (int kb = lane * 4; kb < Kw; kb += 256) {
+            uint4 b[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) b[q] = *reinterpret_cast<const uint4 *>(brow[q] + kb);
+#pragma unroll
+            for (int r = 0; r < MT; ++r) {
+                if (r < M) {
+                    const uint4 a = *reinterpret_cast<const uint4 *>(A + (int64_t)r * Kw + kb);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[r][q] += __builtin_popcount(a.x ^ b[q].x) + __builtin_popcount(a.y ^ b[q].y) +
+                                     __builtin_popcount(a.z ^ b[q].z) + __builtin_popcount(a.w ^ b[q].w);
+                }
             }
         }
+    } else {
+        for (int kb = lane; kb < Kw; kb += 64) {
+            uint32_t b[4];
 #pragma unroll
-        for (int r = 0; r < MT; ++r) {
-            int v = acc[r];
+            for (int q = 0; q < 4; ++q) b[q] = brow[q][kb];
 #pragma unroll
-            for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s);
-            if (lane == 0) xs[r][ol] = K - 2 * v;
+            for (int r = 0; r < MT; ++r) {
+                if (r < M) {
+                    const uint32_t a = A[(int64_t)r * Kw + kb];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[r][q] += __builtin_popcount(a ^ b[q]);
+                }
+            }
         }
+    }
+
+    // halving butterfly: after the exchanges with lane^32 and lane^16 a lane keeps the sum of
+    // output q = 2*bit5 + bit4; the remaining four exchanges finish the sum over 16 lanes.
+#pragma unroll
+    for (int r = 0; r < MT; ++r) {
+        if (r >= M) break;
+        const bool hi5 = (lane & 32) != 0, hi4 = (lane & 16) != 0;
+        const int s0 = hi5 ? acc[r][0] : acc[r][2], s1 = hi5 ? acc[r][1] : acc[r][3];   // what the partner keeps
+        const int k0 = hi5 ? acc[r][2] : acc[r][0], k1 = hi5 ? acc[r][3] : acc[r][1];   // what this lane keeps
+        const int t0 = k0 + __shfl_xor(s0, 32), t1 = k1 + __shfl_xor(s1, 32);
+        int v = (hi4 ? t1 : t0) + __shfl_xor(hi4 ? t0 : t1, 16);
+        v += __shfl_xor(v, 8);
+        v += __shfl_xor(v, 4);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 1);
+        if ((lane & 15) == 0) xs[r][wave * 4 + (lane >> 4)] = K - 2 * v;
     }
     __syncthreads();
 
     const int tid = threadIdx.x;
-    const int r = tid >> 5;       // 8 rows x 32 outputs = 256 threads
-    const int ol = tid & 31;
-    const int64_t o = o_base + ol;
-    const bool ok = (r < MT) && (r < M) && (o < N);
-    const int x = ok ? xs[r < MT ? r : 0][ol] : 0;
-    if (ep.preact && ok) ep.preact[(int64_t)r * N + o] = x;
-    if (ep.packed) {
-        bool bit = false;
-        if (ok) {
-            bit = x > ep.thr[o];
-            if (ep.flip && ep.flip[o]) bit = !bit;
+    if (tid < 256) {                // 8 rows x 32 outputs; waves 0..3 are entirely inside
+        const int r = tid >> 5;
+        const int ol = tid & 31;
+        const int64_t o = o_base + ol;
+        const bool ok = (r < MT) && (r < M) && (o < N);
+        const int x = ok ? xs[r < MT ? r : 0][ol] : 0;
+        if (ep.preact && ok) ep.preact[(int64_t)r * N + o] = x;
+        if (ep.packed) {
+            bool bit = false;
+            if (ok) {
+                bit = x > ep.thr[o];
+                if (ep.flip && ep.flip[o]) bit = !bit;
+            }
+            const unsigned long long mask = __ballot(bit);   // lanes 0-31: row r, 32-63: row r+1
+            const unsigned word = (lane < 32) ? (unsigned)(mask & 0xffffffffull) : (unsigned)(mask >> 32);
+            const int64_t nw = (N + 31) >> 5;
+            if (ol == 0 && r < M && r < MT) ep.packed[(int64_t)r * nw + blockIdx.x] = word;
         }
-        const unsigned long long mask = __ballot(bit);   // lanes 0-31: row r, 32-63: row r+1
-        const unsigned word = (lane < 32) ? (unsigned)(mask & 0xffffffffull) : (unsigned)(mask >> 32);
-        const int64_t nw = (N + 31) >> 5;
-        if (ol == 0 && r < M && r < MT) ep.packed[(int64_t)r * nw + blockIdx.x] = word;
     }
 }
 
@@ -300,7 +341,10 @@ bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint3
     const int kw = (int)((k + 31) / 32);
     if (m <= 8) {
         dim3 grid((unsigned)ceil_div64(n, 32));
-        hipLaunchKernelGGL(bgemv_rows<8>, grid, dim3(256), 0, s, a, b, (int)m, n, kw, (int)k, ep);
+        if ((kw & 3) == 0)
+            hipLaunchKernelGGL((bgemv_rows<8, 4>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep);
+        else
+            hipLaunchKernelGGL((bgemv_rows<8, 1>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep);
         return hip_result(hipGetLastError());
     }
     // largest tile that still fills most of the 256 compute units
