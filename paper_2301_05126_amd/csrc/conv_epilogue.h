@@ -63,13 +63,13 @@ __device__ __forceinline__ int write_lane(int old, unsigned value)
     return old;
 }
 
-// Per-column step parameters of one wave: the threshold of this lane's channel in each of
-// its TN tiles, and wave-wide masks (bit = lane) of the lanes whose channel is flipped /
-// exists.  Loaded once per block.
+// Per-column step parameters of one lane: the threshold of its channel in each of the wave's
+// TN tiles and two flags (bit 0: comparison flipped, bit 1: channel exists).  Loaded once
+// per block; kept in vector registers, the wave-wide masks are rebuilt where they are used.
 template <int TN>
 struct StepCols {
     int thr[TN];
-    unsigned long long flipmask[TN], okmask[TN];
+    int flags[TN];
 };
 
 template <int TN>
@@ -81,18 +81,11 @@ __device__ __forceinline__ StepCols<TN> load_step_cols(const EpiArgs &ep, int ch
         const int col = ch0 + j * 32 + l32;
         const bool cok = col < c_out;
         sc.thr[j] = cok ? ep.thr[col] : 0;
-        sc.flipmask[j] = __ballot(cok && ep.flip && ep.flip[col]);
-        sc.okmask[j] = __ballot(cok);
+        sc.flags[j] = (cok ? 2 : 0) | ((cok && ep.flip && ep.flip[col]) ? 1 : 0);
     }
     return sc;
 }
 
-// Step (+ pool) of one wave's tiles into the block's LDS output tile.
-// out_lds is [output pixel of the block][bw words]; an output pixel is a GEMM row (pool 1)
-// or a window (pool 2); word0 = index, inside the block's bw words, of this wave's first
-// 32 channels.  A compare writes a 64-lane mask whose halves are the packed words of two
-// rows; the words are parked in lanes of a register (v_writelane) and leave with one LDS
-// store per 64 words.  Channels beyond c_out give zero bits.
 // One parked word pair: mask halves -> lanes K and 32 + K of `parked`.
 template <int K>
 __device__ __forceinline__ int park_pair(int parked, unsigned long long m)
@@ -133,7 +126,7 @@ __device__ __forceinline__ void conv_tile_step_to_lds(GetX getx, int row0, int w
     const int k = lane & 31, hf = lane >> 5;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const unsigned long long fm = sc.flipmask[j], om = sc.okmask[j];
+        const unsigned long long fm = __ballot((sc.flags[j] & 1) != 0), om = __ballot((sc.flags[j] & 2) != 0);
         const int thr = sc.thr[j];
         if (pool == 2) {
             // window W = 4i + a4 of this wave -> lanes W (lower rows) and 32 + W

@@ -143,7 +143,11 @@ struct FirstGeomM {
     int lth, ltw, ni, tiles_x, tiles_y, n_co_tiles, n_items;
     int sl, slp, kp;            // bytes of one kernel row, padded to 16, and padded K (multiple of 32)
     int patch_bytes;
+    unsigned mg_cin, mg_pw, mg_ph;   // ceil(2^32 / d) for d = c_in, patch width, patch height
 };
+
+// floor(n / d) for n, d < 2^16 with mg = ceil(2^32 / d) (mg == 0 stands for d == 1): one v_mul_hi_u32.
+__device__ __forceinline__ int div_magic(int n, unsigned mg) { return mg ? (int)__umulhi((unsigned)n, mg) : n; }
 
 // Block = 4 waves x 64 pixels (two 32-row tiles each) x NG groups of 64 channels, taken one
 // group after the other; blocks are persistent (weights staged once, then a grid-stride
@@ -249,11 +253,9 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
                     const int idx = base + u * 256 + t;
                     v[u] = 0;
                     if (idx < total) {
-                        const int c = idx % g.c_in;
-                        int p = idx / g.c_in;
-                        const int px = p % pw; p /= pw;
-                        const int py = p % ph;
-                        const int il = p / ph;
+                        const int p0 = div_magic(idx, g.mg_cin), c = idx - p0 * g.c_in;
+                        const int p1 = div_magic(p0, g.mg_pw), px = p0 - p1 * pw;
+                        const int il = div_magic(p1, g.mg_ph), py = p1 - il * ph;
                         const int y = y0 + py - g.pad, x = x0 + px - g.pad, img = img0 + il;
                         v[u] = g.pad_value;
                         if (img < g.n && y >= 0 && y < g.h && x >= 0 && x < g.w)
@@ -318,7 +320,14 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
             const int ch0 = o_blk + grp * 64;
             if (ep.preact) conv_tile_store_preact<2, TN>(getx, wave * 64, ch0, l32, half, pos, ep.preact);
 #ifndef BNN_X_NOEPI
-            if (ep.packed) conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, lane, sc[grp], ep.pool, Ol);
+            if (ep.packed) {
+                // select this group's parameters without indexing the register array dynamically
+                StepCols<TN> cur = sc[0];
+#pragma unroll
+                for (int q = 1; q < NG; ++q)
+                    if (grp == q) cur = sc[q];
+                conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, lane, cur, ep.pool, Ol);
+            }
 #else
             if (acc[0][0][0] == 0x12345678 && acc[1][1][5] == 77) ep.packed[0] = 1;
 #endif
@@ -430,6 +439,10 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
         g.lth = ts.lth; g.ltw = ts.ltw; g.ni = ts.ni; g.tiles_x = ts.tiles_x; g.tiles_y = ts.tiles_y;
         const int64_t pbytes = (int64_t)g.ni * ((1 << g.lth) + kh - 1) * ((1 << g.ltw) + kw - 1) * c_in;
         g.patch_bytes = (int)((pbytes + 32 + 15) & ~15LL);       // slack: reads run past short rows
+        auto magic = [](int d) { return d == 1 ? 0u : (unsigned)((0x100000000ULL + d - 1) / d); };
+        g.mg_cin = magic(c_in);
+        g.mg_pw = magic((1 << g.ltw) + kw - 1);
+        g.mg_ph = magic((1 << g.lth) + kh - 1);
         if (g.kp <= 128 && pbytes <= 24 * 1024) {
             const bnn_status st = (c_out > 64) ? launch_first_mfma<2>(in, wt, g, ep, s)
                                                : launch_first_mfma<1>(in, wt, g, ep, s);
