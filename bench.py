@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--workload", default="vgg_small_b256", choices=sorted(WORKLOADS))
     ap.add_argument("--no-extras", action="store_true", help="skip sweeps / latency / CPU baseline")
     ap.add_argument("--cpu-images", type=int, default=160, help="images in the CPU-oracle sample")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -110,6 +112,15 @@ def main():
     xd = to_device(imgs)
     bmacs_img = W.model_binary_macs(layers)
     i8macs_img = W.model_int8_macs(layers)
+
+    if args.pmc_calibration:
+        # known traffic: 3 x (256 MiB read + 256 MiB written) by a plain elementwise copy kernel
+        src = torch.arange(64 * 1024 * 1024, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region: K steps of the whole model, inputs resident in HBM
     ms_ev, ms_host = time_steps(lambda: dm.run(xd, P.RUN_STREAM), args.steps, args.warmup, torch)

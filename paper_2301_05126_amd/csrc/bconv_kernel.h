@@ -95,7 +95,11 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
 
+    // XCD-aware order: hardware deals consecutive block ids round-robin to the 8 XCDs (one L2
+    // each); renumber so that blocks sharing an input patch (the channel tiles of one pixel
+    // tile) run on the same XCD and the patch is fetched from HBM once.
     int bid = blockIdx.x;
+    if ((gridDim.x & 7) == 0) bid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
     const int co_tile = bid % g.n_co_tiles; bid /= g.n_co_tiles;
     const int tile_x = bid % g.tiles_x;     bid /= g.tiles_x;
     const int tile_y = bid % g.tiles_y;     bid /= g.tiles_y;

@@ -83,8 +83,12 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
     const int lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
-    const int64_t m0 = (int64_t)(blockIdx.x / nbn) * BM;
-    const int64_t n0 = (int64_t)(blockIdx.x % nbn) * BN;
+    // XCD-aware order (consecutive block ids go round-robin to the 8 XCDs / L2s): renumber so
+    // that the blocks walking one row block of A share an L2.
+    unsigned bid = blockIdx.x;
+    if ((gridDim.x & 7) == 0) bid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int64_t m0 = (int64_t)(bid / nbn) * BM;
+    const int64_t n0 = (int64_t)(bid % nbn) * BN;
 
     v16f acc[TM][TN];
 #pragma unroll

@@ -176,7 +176,10 @@ __device__ __forceinline__ void conv_tile_copy_out(const uint32_t *out_lds, int 
             uint32_t *dst = ep.packed + (((int64_t)img * oh + y) * ow + x) * cwo + blk_word0;
             const uint32_t *sp = out_lds + src * BW;
             if (vec_ok) {
-                if (BW == 4) *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(sp);
+                if (BW == 8) {
+                    reinterpret_cast<uint4 *>(dst)[0] = reinterpret_cast<const uint4 *>(sp)[0];
+                    reinterpret_cast<uint4 *>(dst)[1] = reinterpret_cast<const uint4 *>(sp)[1];
+                } else if (BW == 4) *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(sp);
                 else if (BW == 2) *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(sp);
                 else {
 #pragma unroll
