@@ -67,16 +67,21 @@ const char *bnn_version(void);
  * Step layer (+ optional max-pool) fused behind a conv / FC layer.
  * Paper Sec. II-A: the step layer is batch-norm followed by the binary activation,
  * evaluated at inference as a comparison with a signed-integer threshold; the maxpool
- * layer takes the maximum over 2x2 windows.  Applied in the order step, then pool:
+ * layer takes the maximum over 2x2 windows.
  *   bit[c] = (x[c] > thr[c]) xor (flip[c] != 0)     strict '>', thr int32
- *   pool == 2: OR of the four bits of each 2x2 / stride-2 window (= max of +-1 values)
+ *   pool == 2, pool_first == 0: step, then OR of the four bits of each 2x2 / stride-2 window
+ *                               (= max of the +-1 values; the benchmark configurations' order)
+ *   pool == 2, pool_first == 1: max of the four int32 pre-activations of the window, then the
+ *                               step (the order of the paper's model tables, C -> MP -> S)
+ * The two orders agree on channels with flip == 0 and differ where flip != 0.
  * thr:  device, int32 [c_out].   flip: device, uint8 [c_out], or NULL for "no flips".
- * pool: 1 or 2.
+ * pool: 1 or 2.  pool_first: 0 or 1 (ignored when pool == 1).
  */
 typedef struct bnn_epilogue {
     const int32_t *thr;
     const uint8_t *flip;
     int pool;
+    int pool_first;
 } bnn_epilogue;
 
 /*
@@ -138,14 +143,14 @@ bnn_status bnn_fc_binary(const uint32_t *a_dev, int64_t m, int64_t k, const uint
 
 /*
  * Stand-alone step (+ pool) layer on int32 pre-activations (paper Sec. II-A step and
- * maxpool layers), same arithmetic as bnn_epilogue:
+ * maxpool layers), same arithmetic and same meaning of pool / pool_first as bnn_epilogue:
  *   preact_dev: device, int32 [n][h][w][c];  thr_dev int32 [c];  flip_dev uint8 [c] or NULL.
  *   packed_out_dev: device, uint32 [n][h/pool][w/pool][ceil(c/32)].
  * Errors: NULL, SHAPE (pool not 1|2, odd h/w with pool 2), ALIGN.
  */
 bnn_status bnn_threshold_sign_maxpool(const int32_t *preact_dev, int n, int h, int w, int c,
                                       const int32_t *thr_dev, const uint8_t *flip_dev, int pool,
-                                      uint32_t *packed_out_dev, void *stream);
+                                      int pool_first, uint32_t *packed_out_dev, void *stream);
 
 /* ------------------------------------------------------------------ whole model ----- */
 
@@ -168,6 +173,7 @@ typedef struct bnn_layer_desc {
     int pad_value;          /* CONV_FIRST_INT8 only                                        */
     int has_step;           /* 1 for hidden layers, 0 for the last layer                   */
     int pool;               /* 1 or 2 (conv layers only; requires has_step)                */
+    int pool_first;         /* 0: step then pool, 1: pool then step (see bnn_epilogue)     */
     const void *weights_dev;/* int8 [c_out][kh][kw][c_in] for CONV_FIRST_INT8, else packed */
     const int32_t *thr_dev; /* [c_out], required iff has_step                              */
     const uint8_t *flip_dev;/* [c_out] or NULL                                             */

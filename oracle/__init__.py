@@ -134,12 +134,13 @@ def maxpool2(x):
     return out
 
 
-def run_layer(L, act, first_pad_value=-1):
+def run_layer(L, act, first_pad_value=-1, pool_first=False):
     """One model layer: conv/FC -> [step -> [pool]].  Returns (preact int32, act_out).
 
     `act` is int8: NHWC pixels for the first layer, +-1 NHWC (or [n,k]) afterwards.
     act_out is +-1 int8 (NHWC or [n,c]) for hidden layers and None for the logits layer.
-    Order is step then pool (the benchmark configurations' order).
+    Order is step then pool (the benchmark configurations' order) unless pool_first, which
+    pools the integer pre-activations and then steps (the order of the paper's Tab. I / II).
     """
     if L.kind == "fc_binary":
         a = act.reshape(act.shape[0], -1)          # flatten: (h, w, c), c fastest
@@ -153,19 +154,22 @@ def run_layer(L, act, first_pad_value=-1):
         pre = pre4
     if not L.step:
         return pre, None
-    s = step(pre4, L.thr, L.flip)
-    if L.pool == 2:
-        s = maxpool2(s)
+    if L.pool == 2 and pool_first:
+        s = step(maxpool2(pre4), L.thr, L.flip)
+    else:
+        s = step(pre4, L.thr, L.flip)
+        if L.pool == 2:
+            s = maxpool2(s)
     return pre, s
 
 
-def run_model(layers, images, first_pad_value=-1):
+def run_model(layers, images, first_pad_value=-1, pool_first=False):
     """Whole model.  Returns (logits int32 [n, classes], per-layer list of (preact, act))."""
     act = np.ascontiguousarray(images, dtype=np.int8)
     trace = []
     pre = None
     for L in layers:
-        pre, nxt = run_layer(L, act, first_pad_value)
+        pre, nxt = run_layer(L, act, first_pad_value, pool_first)
         trace.append((pre, nxt))
         if nxt is not None:
             act = nxt

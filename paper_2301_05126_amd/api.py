@@ -21,13 +21,13 @@ LAYER_CONV_FIRST_INT8, LAYER_CONV_BINARY, LAYER_FC_BINARY = 0, 1, 2
 
 
 class Epilogue(C.Structure):
-    _fields_ = [("thr", C.c_void_p), ("flip", C.c_void_p), ("pool", C.c_int)]
+    _fields_ = [("thr", C.c_void_p), ("flip", C.c_void_p), ("pool", C.c_int), ("pool_first", C.c_int)]
 
 
 class LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int), ("c_in", C.c_int), ("c_out", C.c_int),
                 ("kh", C.c_int), ("kw", C.c_int), ("pad", C.c_int), ("pad_value", C.c_int),
-                ("has_step", C.c_int), ("pool", C.c_int),
+                ("has_step", C.c_int), ("pool", C.c_int), ("pool_first", C.c_int),
                 ("weights_dev", C.c_void_p), ("thr_dev", C.c_void_p), ("flip_dev", C.c_void_p),
                 ("preact_tap_dev", C.c_void_p), ("packed_tap_dev", C.c_void_p)]
 
@@ -49,7 +49,7 @@ _lib.bnn_conv_first_int8.argtypes = [_vp, _i, _i, _i, _i, _vp, _i, _i, _i, _i, _
                                      C.POINTER(Epilogue), _vp, _vp, _vp]
 _lib.bnn_conv_binary.argtypes = [_vp, _i, _i, _i, _i, _vp, _i, C.POINTER(Epilogue), _vp, _vp, _vp]
 _lib.bnn_fc_binary.argtypes = [_vp, _i64, _i64, _vp, _i64, C.POINTER(Epilogue), _vp, _vp, _vp]
-_lib.bnn_threshold_sign_maxpool.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp, _i, _vp, _vp]
+_lib.bnn_threshold_sign_maxpool.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp, _i, _i, _vp, _vp]
 _lib.bnn_model_create.argtypes = [C.POINTER(LayerDesc), _i, _i, _i, _i, _i, C.POINTER(_vp)]
 _lib.bnn_model_workspace_bytes.argtypes = [_vp]
 _lib.bnn_model_workspace_bytes.restype = C.c_size_t
@@ -108,10 +108,10 @@ def _check(st, where):
         raise BnnError(st, where)
 
 
-def _ep(thr, flip, pool):
+def _ep(thr, flip, pool, pool_first=0):
     if thr is None:
         return None
-    return C.byref(Epilogue(_ptr(thr), _ptr(flip), int(pool)))
+    return C.byref(Epilogue(_ptr(thr), _ptr(flip), int(pool), int(pool_first)))
 
 
 def bnn_pack_bits(src, rows, k, dst, stream=None):
@@ -119,15 +119,16 @@ def bnn_pack_bits(src, rows, k, dst, stream=None):
 
 
 def bnn_conv_first_int8(inp, n, h, w, c_in, wt, c_out, kh, kw, pad, pad_value,
-                        thr=None, flip=None, pool=1, preact_out=None, packed_out=None, stream=None):
+                        thr=None, flip=None, pool=1, pool_first=0, preact_out=None, packed_out=None,
+                        stream=None):
     _check(_lib.bnn_conv_first_int8(_ptr(inp), n, h, w, c_in, _ptr(wt), c_out, kh, kw, pad, pad_value,
-                                    _ep(thr, flip, pool), _ptr(preact_out), _ptr(packed_out),
+                                    _ep(thr, flip, pool, pool_first), _ptr(preact_out), _ptr(packed_out),
                                     _stream(stream)), "bnn_conv_first_int8")
 
 
-def bnn_conv_binary(inp, n, h, w, c_in, wt, c_out, thr=None, flip=None, pool=1,
+def bnn_conv_binary(inp, n, h, w, c_in, wt, c_out, thr=None, flip=None, pool=1, pool_first=0,
                     preact_out=None, packed_out=None, stream=None):
-    _check(_lib.bnn_conv_binary(_ptr(inp), n, h, w, c_in, _ptr(wt), c_out, _ep(thr, flip, pool),
+    _check(_lib.bnn_conv_binary(_ptr(inp), n, h, w, c_in, _ptr(wt), c_out, _ep(thr, flip, pool, pool_first),
                                 _ptr(preact_out), _ptr(packed_out), _stream(stream)), "bnn_conv_binary")
 
 
@@ -136,9 +137,9 @@ def bnn_fc_binary(a, m, k, b, n, thr=None, flip=None, c_out=None, packed_out=Non
                               _ptr(packed_out), _stream(stream)), "bnn_fc_binary")
 
 
-def bnn_threshold_sign_maxpool(preact, n, h, w, c, thr, flip, pool, packed_out, stream=None):
+def bnn_threshold_sign_maxpool(preact, n, h, w, c, thr, flip, pool, packed_out, pool_first=0, stream=None):
     _check(_lib.bnn_threshold_sign_maxpool(_ptr(preact), n, h, w, c, _ptr(thr), _ptr(flip), pool,
-                                           _ptr(packed_out), _stream(stream)),
+                                           int(pool_first), _ptr(packed_out), _stream(stream)),
            "bnn_threshold_sign_maxpool")
 
 

@@ -109,32 +109,47 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     const int o_blk = co_tile * BN;
     const int pw = tw + 2, ph = th + 2;
 
-    // ---- stage the input patch (halo included; outside the image / beyond cw = zero words)
+    // per-channel step parameters: issued first so their latency hides behind the main loop
+    StepCols<TN> sc;
+    if (ep.packed) sc = load_step_cols<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
+
+    // ---- stage the input patch (halo included; outside the image / beyond cw = zero words).
+    // Four units per thread are loaded before any is stored, so the loads overlap.
     {
         constexpr int UPP = CWP / V;                  // units per pixel
         const int total = g.ni * ph * pw * UPP;
         const bool vec_ok = (g.cw % V) == 0;
-        for (int idx = t; idx < total; idx += 256) {
-            const int u = idx % UPP;
-            int p = idx / UPP;
-            const int px = p % pw; p /= pw;
-            const int py = p % ph;
-            const int il = p / ph;
-            const int y = y0 + py - 1, x = x0 + px - 1, img = img0 + il;
-            vec_t v;
+        for (int base = 0; base < total; base += 256 * 4) {
+            vec_t v[4];
 #pragma unroll
-            for (int q = 0; q < V; ++q) vec_set(v, q, 0u);
-            if (img < g.n && y >= 0 && y < g.h && x >= 0 && x < g.w) {
-                const uint32_t *src = in + (((int64_t)img * g.h + y) * g.w + x) * g.cw + u * V;
-                if (vec_ok) {
-                    if (u * V < g.cw) v = *reinterpret_cast<const vec_t *>(src);
-                } else {
+            for (int k = 0; k < 4; ++k) {
+                const int idx = base + k * 256 + t;
 #pragma unroll
-                    for (int q = 0; q < V; ++q)
-                        if (u * V + q < g.cw) vec_set(v, q, src[q]);
+                for (int q = 0; q < V; ++q) vec_set(v[k], q, 0u);
+                if (idx < total) {
+                    const int u = idx % UPP;
+                    int p = idx / UPP;
+                    const int px = p % pw; p /= pw;
+                    const int py = p % ph;
+                    const int il = p / ph;
+                    const int y = y0 + py - 1, x = x0 + px - 1, img = img0 + il;
+                    if (img < g.n && y >= 0 && y < g.h && x >= 0 && x < g.w) {
+                        const uint32_t *src = in + (((int64_t)img * g.h + y) * g.w + x) * g.cw + u * V;
+                        if (vec_ok) {
+                            if (u * V < g.cw) v[k] = *reinterpret_cast<const vec_t *>(src);
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < V; ++q)
+                                if (u * V + q < g.cw) vec_set(v[k], q, src[q]);
+                        }
+                    }
                 }
             }
-            *reinterpret_cast<vec_t *>(Ps + idx * V) = v;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int idx = base + k * 256 + t;
+                if (idx < total) *reinterpret_cast<vec_t *>(Ps + idx * V) = v[k];
+            }
         }
     }
 
@@ -265,8 +280,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         // bits -> LDS tile [output pixel][2*TN words] (reusing the weight buffer) -> coalesced stores
         constexpr int BW = 2 * TN;
         __syncthreads();                      // every wave is done with the weight chunk
-        const StepCols<TN> sc = load_step_cols<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
-        conv_tile_step_to_lds<TM, TN>(getx, wm * TM * 32, wn * TN, BW, lane, sc, ep.pool, Bs);
+        conv_tile_step_to_lds<TM, TN>(getx, wm * TM * 32, wn * TN, BW, lane, sc, ep.pool, ep.pool_first != 0, Bs);
         __syncthreads();
         conv_tile_copy_out<BW>(Bs, 64 * TM, o_blk >> 5, pos, ep, t);
     }
@@ -322,7 +336,7 @@ template <int WPH>
 bnn_status launch_wph(const uint32_t *in, const uint32_t *wt, int n, int h, int w, int c_in, int c_out,
                       const EpiArgs &ep, hipStream_t s)
 {
-    const int64_t want = 192;
+    const int64_t want = 512;     // two resident blocks per compute unit
     if (blocks_one<4, 2, WPH>(n, h, w, c_in, c_out) >= want)
         return launch_one<4, 2, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
     if (blocks_one<2, 2, WPH>(n, h, w, c_in, c_out) >= want)

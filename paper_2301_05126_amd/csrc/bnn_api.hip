@@ -25,7 +25,7 @@ static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t
 static bnn_status check_epilogue(const bnn_epilogue *ep, const void *raw_out, const void *packed_out,
                                  int ho, int wo, bool pool_allowed, EpiArgs *out)
 {
-    out->thr = nullptr; out->flip = nullptr; out->pool = 1;
+    out->thr = nullptr; out->flip = nullptr; out->pool = 1; out->pool_first = 0;
     out->preact = (int32_t *)raw_out;
     out->packed = nullptr;
     if (!ep) {
@@ -35,12 +35,14 @@ static bnn_status check_epilogue(const bnn_epilogue *ep, const void *raw_out, co
     }
     if (!ep->thr || !packed_out) return BNN_ERR_NULL;
     if (ep->pool != 1 && ep->pool != 2) return BNN_ERR_SHAPE;
+    if (ep->pool_first != 0 && ep->pool_first != 1) return BNN_ERR_SHAPE;
     if (ep->pool == 2 && (!pool_allowed || (ho & 1) || (wo & 1))) return BNN_ERR_SHAPE;
     if (!aligned16(ep->thr) || !aligned16(packed_out) || (raw_out && !aligned16(raw_out)))
         return BNN_ERR_ALIGN;
     out->thr = ep->thr;
     out->flip = ep->flip;
     out->pool = ep->pool;
+    out->pool_first = (ep->pool == 2) ? ep->pool_first : 0;
     out->packed = (uint32_t *)packed_out;
     return BNN_OK;
 }
@@ -80,14 +82,16 @@ bnn_status bnn_pack_bits(const int8_t *src_dev, int64_t rows, int64_t k, uint32_
 
 bnn_status bnn_threshold_sign_maxpool(const int32_t *preact_dev, int n, int h, int w, int c,
                                       const int32_t *thr_dev, const uint8_t *flip_dev, int pool,
-                                      uint32_t *packed_out_dev, void *stream)
+                                      int pool_first, uint32_t *packed_out_dev, void *stream)
 {
     if (!preact_dev || !thr_dev || !packed_out_dev) return BNN_ERR_NULL;
     if (n < 0 || h <= 0 || w <= 0 || c <= 0) return BNN_ERR_SHAPE;
     if (pool != 1 && pool != 2) return BNN_ERR_SHAPE;
+    if (pool_first != 0 && pool_first != 1) return BNN_ERR_SHAPE;
     if (pool == 2 && ((h & 1) || (w & 1))) return BNN_ERR_SHAPE;
     if (!aligned16(preact_dev) || !aligned16(thr_dev) || !aligned16(packed_out_dev)) return BNN_ERR_ALIGN;
-    return launch_threshold_sign_maxpool(preact_dev, n, h, w, c, thr_dev, flip_dev, pool, packed_out_dev,
+    return launch_threshold_sign_maxpool(preact_dev, n, h, w, c, thr_dev, flip_dev, pool,
+                                         pool == 2 ? pool_first : 0, packed_out_dev,
                                          (hipStream_t)stream);
 }
 
@@ -191,6 +195,7 @@ bnn_status bnn_model_create(const bnn_layer_desc *layers, int n_layers, int batc
             if (!L.thr_dev) { st = BNN_ERR_NULL; break; }
             if (!aligned16(L.thr_dev)) { st = BNN_ERR_ALIGN; break; }
             if (L.pool != 1 && L.pool != 2) { st = BNN_ERR_SHAPE; break; }
+            if (L.pool_first != 0 && L.pool_first != 1) { st = BNN_ERR_SHAPE; break; }
         }
         if ((L.preact_tap_dev && !aligned16(L.preact_tap_dev)) ||
             (L.packed_tap_dev && !aligned16(L.packed_tap_dev))) { st = BNN_ERR_ALIGN; break; }
@@ -269,6 +274,7 @@ static bnn_status enqueue_layer(bnn_model *m, int l, const void *src, void *dst,
     const bnn_layer_desc &L = m->layers[l];
     bnn_epilogue ep;
     ep.thr = L.thr_dev; ep.flip = L.flip_dev; ep.pool = L.has_step ? L.pool : 1;
+    ep.pool_first = L.pool_first;
     const bnn_epilogue *epp = L.has_step ? &ep : nullptr;
     int32_t *raw = L.has_step ? (taps ? L.preact_tap_dev : nullptr) : logits;
     uint32_t *packed = L.has_step ? (uint32_t *)dst : nullptr;

@@ -18,6 +18,7 @@ struct EpiArgs {
     int32_t *preact;
     uint32_t *packed;
     int pool;              // 1 or 2
+    int pool_first;        // 1: max of the int32 window first, then the step
 };
 
 // Records a HIP error for bnn_last_hip_error() and returns BNN_ERR_HIP, or BNN_OK.
@@ -29,7 +30,7 @@ bnn_status launch_pack_bits(const int8_t *src, int64_t rows, int64_t k, uint32_t
                             hipStream_t s);
 bnn_status launch_threshold_sign_maxpool(const int32_t *x, int n, int h, int w, int c,
                                          const int32_t *thr, const uint8_t *flip, int pool,
-                                         uint32_t *out, hipStream_t s);
+                                         int pool_first, uint32_t *out, hipStream_t s);
 bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
                             const EpiArgs &ep, hipStream_t s);
 bnn_status launch_conv_binary(const uint32_t *in, int n, int h, int w, int c_in,

@@ -106,13 +106,22 @@ __device__ __forceinline__ int park_rows(GetX getx, int i, int j, int thr, unsig
 
 template <int TM, int TN, typename GetX, int... W>
 __device__ __forceinline__ int park_windows(GetX getx, int j, int thr, unsigned long long fm,
-                                            unsigned long long om, std::integer_sequence<int, W...>)
+                                            unsigned long long om, bool pool_first,
+                                            std::integer_sequence<int, W...>)
 {
     int parked = 0;
     auto window = [&](int i, int a4) {
         unsigned long long m = 0;
+        if (pool_first) {
+            // max of the four pre-activations, then one comparison
+            int x = getx(i, j, a4 * 4);
 #pragma unroll
-        for (int sub = 0; sub < 4; ++sub) m |= __ballot(getx(i, j, a4 * 4 + sub) > thr) ^ fm;
+            for (int sub = 1; sub < 4; ++sub) x = max(x, getx(i, j, a4 * 4 + sub));
+            m = __ballot(x > thr) ^ fm;
+        } else {
+#pragma unroll
+            for (int sub = 0; sub < 4; ++sub) m |= __ballot(getx(i, j, a4 * 4 + sub) > thr) ^ fm;
+        }
         return m & om;
     };
     ((parked = park_pair<W>(parked, window(W / 4, W % 4))), ...);
@@ -121,7 +130,8 @@ __device__ __forceinline__ int park_windows(GetX getx, int j, int thr, unsigned 
 
 template <int TM, int TN, typename GetX>
 __device__ __forceinline__ void conv_tile_step_to_lds(GetX getx, int row0, int word0, int bw, int lane,
-                                                      const StepCols<TN> &sc, int pool, uint32_t *out_lds)
+                                                      const StepCols<TN> &sc, int pool, bool pool_first,
+                                                      uint32_t *out_lds)
 {
     const int k = lane & 31, hf = lane >> 5;
 #pragma unroll
@@ -130,7 +140,7 @@ __device__ __forceinline__ void conv_tile_step_to_lds(GetX getx, int row0, int w
         const int thr = sc.thr[j];
         if (pool == 2) {
             // window W = 4i + a4 of this wave -> lanes W (lower rows) and 32 + W
-            const int parked = park_windows<TM, TN>(getx, j, thr, fm, om, std::make_integer_sequence<int, TM * 4>{});
+            const int parked = park_windows<TM, TN>(getx, j, thr, fm, om, pool_first, std::make_integer_sequence<int, TM * 4>{});
             // lane (k, hf) holds window (row0/4) + 8*(k/4) + 2*(k%4) + hf
             if (k < TM * 4) out_lds[((row0 >> 2) + (k >> 2) * 8 + (k & 3) * 2 + hf) * bw + word0 + j] = (uint32_t)parked;
         } else {

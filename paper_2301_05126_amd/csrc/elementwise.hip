@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void pack_bits_generic(const int8_t *__restric
 
 struct StepGeom {
     int n, h, w, c;
-    int ho, wo, cwo, pool;
+    int ho, wo, cwo, pool, pool_first;
 };
 
 // One thread per (output pixel, 8-channel group); four neighbouring lanes own one word.
@@ -89,6 +89,9 @@ __global__ __launch_bounds__(256) void step_pool_kernel(const int32_t *__restric
                     if (ok) valid |= 1u << j;
                     if (ok && flip && flip[c0 + j]) fm |= 1u << j;
                 }
+                int vmax[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) vmax[j] = INT32_MIN;
                 for (int sy = 0; sy < g.pool; ++sy)
                     for (int sx = 0; sx < g.pool; ++sx) {
                         const int y = yo * g.pool + sy, xx = xo * g.pool + sx;
@@ -105,9 +108,19 @@ __global__ __launch_bounds__(256) void step_pool_kernel(const int32_t *__restric
                         }
                         unsigned b = 0;
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) b |= (v[j] > t[j] ? 1u : 0u) << j;
+                        for (int j = 0; j < 8; ++j) {
+                            b |= (v[j] > t[j] ? 1u : 0u) << j;
+                            vmax[j] = max(vmax[j], v[j]);
+                        }
                         byte |= (b ^ fm) & valid;
                     }
+                if (g.pool_first) {
+                    // paper order: max of the window's pre-activations, then the step
+                    unsigned b = 0;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) b |= (vmax[j] > t[j] ? 1u : 0u) << j;
+                    byte = (b ^ fm) & valid;
+                }
             }
         }
         unsigned word = byte << (8 * (threadIdx.x & 3));
@@ -144,12 +157,13 @@ bnn_status launch_pack_bits(const int8_t *src, int64_t rows, int64_t k, uint32_t
 }
 
 bnn_status launch_threshold_sign_maxpool(const int32_t *x, int n, int h, int w, int c, const int32_t *thr,
-                                         const uint8_t *flip, int pool, uint32_t *out, hipStream_t s)
+                                         const uint8_t *flip, int pool, int pool_first, uint32_t *out,
+                                         hipStream_t s)
 {
     if (n == 0) return BNN_OK;
     StepGeom g;
     g.n = n; g.h = h; g.w = w; g.c = c;
-    g.pool = pool; g.ho = h / pool; g.wo = w / pool; g.cwo = (c + 31) / 32;
+    g.pool = pool; g.pool_first = pool_first; g.ho = h / pool; g.wo = w / pool; g.cwo = (c + 31) / 32;
     const int64_t total = (int64_t)n * g.ho * g.wo * g.cwo * 4;
     if ((c & 7) == 0)
         hipLaunchKernelGGL(step_pool_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, x, thr, flip, g, out);

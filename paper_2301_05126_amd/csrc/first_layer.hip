@@ -113,6 +113,16 @@ __global__ __launch_bounds__(256) void conv_first_kernel(const int8_t *__restric
             if (o0 + o < g.c_out) dst[o] = acc[o];
     }
     if (ep.packed) {
+        if (g.pool == 2 && ep.pool_first) {
+            // pool the int32 pre-activations of the window (four neighbouring lanes) first
+#pragma unroll
+            for (int o = 0; o < 32; ++o) {
+                int v = live ? acc[o] : INT32_MIN;
+                v = max(v, __shfl_xor(v, 1));
+                v = max(v, __shfl_xor(v, 2));
+                acc[o] = v;
+            }
+        }
         unsigned word = 0;
 #pragma unroll
         for (int o = 0; o < 32; ++o) {
@@ -326,7 +336,7 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
 #pragma unroll
                 for (int q = 1; q < NG; ++q)
                     if (grp == q) cur = sc[q];
-                conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, lane, cur, ep.pool, Ol);
+                conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, lane, cur, ep.pool, ep.pool_first != 0, Ol);
             }
 #else
             if (acc[0][0][0] == 0x12345678 && acc[1][1][5] == 77) ep.packed[0] = 1;

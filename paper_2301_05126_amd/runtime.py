@@ -33,7 +33,8 @@ class DeviceModel:
     workspace and logits buffer.  With taps=True every layer also gets buffers that
     receive its int32 pre-activations and packed activations."""
 
-    def __init__(self, layers, batch, in_shape, first_pad_value=-1, taps=False, device="cuda:0"):
+    def __init__(self, layers, batch, in_shape, first_pad_value=-1, taps=False, device="cuda:0",
+                 pool_first=False):
         if not torch.cuda.is_available():
             raise RuntimeError("libbnn needs a GPU; there is no CPU path")
         self.layers, self.batch, self.device = layers, batch, device
@@ -62,7 +63,7 @@ class DeviceModel:
             self.packed_taps.append(ktap)
             descs.append(P.LayerDesc(
                 KINDS[L.kind], L.c_in, L.c_out, L.kh, L.kw, L.pad, first_pad_value,
-                1 if L.step else 0, L.pool, wdev.data_ptr(),
+                1 if L.step else 0, L.pool, 1 if pool_first else 0, wdev.data_ptr(),
                 thr.data_ptr() if thr is not None else None,
                 flip.data_ptr() if flip is not None else None,
                 ptap.data_ptr() if ptap is not None else None,

@@ -59,7 +59,7 @@ def test_pack_bits_validation(lib):
 
 def test_fc_validation(lib):
     f = lib.api._lib.bnn_fc_binary
-    ep = lib.Epilogue(P16, None, 1)
+    ep = lib.Epilogue(P16, None, 1, 0)
     assert f(None, 4, 64, P16, 8, None, P16, None, None) == NULL
     assert f(P16, 4, 64, None, 8, None, P16, None, None) == NULL
     assert f(P16, 4, 64, P16, 8, None, None, None, None) == NULL          # raw output required
@@ -69,9 +69,9 @@ def test_fc_validation(lib):
     assert f(P16, 4, 64, P16, 0, None, P16, None, None) == SHAPE
     assert f(P8, 4, 64, P16, 8, None, P16, None, None) == ALIGN
     assert f(P16, 4, 64, P16, 8, None, P8, None, None) == ALIGN
-    bad_pool = lib.Epilogue(P16, None, 2)
+    bad_pool = lib.Epilogue(P16, None, 2, 0)
     assert f(P16, 4, 64, P16, 8, C.byref(bad_pool), None, P16, None) == SHAPE
-    no_thr = lib.Epilogue(None, None, 1)
+    no_thr = lib.Epilogue(None, None, 1, 0)
     assert f(P16, 4, 64, P16, 8, C.byref(no_thr), None, P16, None) == NULL
 
 
@@ -81,10 +81,12 @@ def test_conv_validation(lib):
     assert f(P16, 1, 0, 8, 32, P16, 32, None, P16, None, None) == SHAPE
     assert f(P16, 1, 8, 8, 32, P16, 0, None, P16, None, None) == SHAPE
     assert f(P16, 1, 8, 8, 32, P8, 32, None, P16, None, None) == ALIGN
-    pool = lib.Epilogue(P16, None, 2)
+    pool = lib.Epilogue(P16, None, 2, 0)
     assert f(P16, 1, 7, 8, 32, P16, 32, C.byref(pool), None, P16, None) == SHAPE   # odd height
-    pool3 = lib.Epilogue(P16, None, 3)
+    pool3 = lib.Epilogue(P16, None, 3, 0)
     assert f(P16, 1, 8, 8, 32, P16, 32, C.byref(pool3), None, P16, None) == SHAPE
+    bad_order = lib.Epilogue(P16, None, 2, 5)
+    assert f(P16, 1, 8, 8, 32, P16, 32, C.byref(bad_order), None, P16, None) == SHAPE
     assert f(P16, 1, 32, 32, 1 << 16, P16, 32, None, P16, None, None) == UNSUP     # patch > LDS
     g = lib.api._lib.bnn_conv_first_int8
     assert g(None, 1, 8, 8, 1, P16, 32, 3, 3, 1, -1, None, P16, None, None) == NULL
@@ -96,12 +98,13 @@ def test_conv_validation(lib):
 
 def test_step_validation(lib):
     f = lib.api._lib.bnn_threshold_sign_maxpool
-    assert f(None, 1, 4, 4, 8, P16, None, 1, P16, None) == NULL
-    assert f(P16, 1, 4, 4, 8, None, None, 1, P16, None) == NULL
-    assert f(P16, 1, 4, 4, 8, P16, None, 3, P16, None) == SHAPE
-    assert f(P16, 1, 3, 4, 8, P16, None, 2, P16, None) == SHAPE
-    assert f(P16, 1, 4, 4, 0, P16, None, 1, P16, None) == SHAPE
-    assert f(P16, 1, 4, 4, 8, P16, None, 1, P8, None) == ALIGN
+    assert f(None, 1, 4, 4, 8, P16, None, 1, 0, P16, None) == NULL
+    assert f(P16, 1, 4, 4, 8, None, None, 1, 0, P16, None) == NULL
+    assert f(P16, 1, 4, 4, 8, P16, None, 3, 0, P16, None) == SHAPE
+    assert f(P16, 1, 3, 4, 8, P16, None, 2, 0, P16, None) == SHAPE
+    assert f(P16, 1, 4, 4, 8, P16, None, 2, 2, P16, None) == SHAPE
+    assert f(P16, 1, 4, 4, 0, P16, None, 1, 0, P16, None) == SHAPE
+    assert f(P16, 1, 4, 4, 8, P16, None, 1, 0, P8, None) == ALIGN
 
 
 def _vgg_descs(lib, first_kind=None, last_step=0):
@@ -111,7 +114,7 @@ def _vgg_descs(lib, first_kind=None, last_step=0):
     descs = []
     for L in layers:
         d = lib.LayerDesc(kinds[L.kind], L.c_in, L.c_out, L.kh, L.kw, L.pad, -1,
-                          1 if L.step else 0, L.pool, P16, P16 if L.step else None, None, None, None)
+                          1 if L.step else 0, L.pool, 0, P16, P16 if L.step else None, None, None, None)
         descs.append(d)
     return descs
 

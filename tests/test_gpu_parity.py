@@ -69,6 +69,12 @@ def test_threshold_sign_maxpool(n, h, w, c, pool, use_flip):
     if pool == 2:
         s = oracle.maxpool2(s)
     np.testing.assert_array_equal(host_u32(out), pack_pm1(s))
+    if pool == 2:
+        # the paper's order: pool the integers, then step
+        out2 = fill_i32((n, h // 2, w // 2, (c + 31) // 32), -1)
+        P.bnn_threshold_sign_maxpool(dev(x), n, h, w, c, dev(thr), dev(flip) if use_flip else None, 2, out2,
+                                     pool_first=1)
+        np.testing.assert_array_equal(host_u32(out2), pack_pm1(oracle.step(oracle.maxpool2(x), thr, flip)))
 
 
 # ------------------------------------------------------------------------- fc_binary
@@ -116,7 +122,9 @@ def test_fc_binary_with_gpu_packed_operands_and_empty_batch():
 CONV_SHAPES = [(1, 4, 4, 32, 8, 1), (2, 8, 8, 64, 64, 2), (3, 14, 14, 64, 64, 2), (2, 16, 16, 128, 256, 1),
                (1, 32, 32, 128, 128, 2), (2, 8, 8, 256, 512, 1), (5, 8, 8, 512, 512, 2), (1, 5, 7, 32, 40, 1),
                (2, 3, 3, 96, 130, 1), (1, 1, 1, 32, 32, 1), (3, 2, 2, 64, 16, 2), (2, 6, 6, 40, 24, 1),
-               (3, 4, 4, 512, 512, 2), (1, 20, 36, 128, 64, 2), (17, 4, 4, 128, 128, 1)]
+               (3, 4, 4, 512, 512, 2), (1, 20, 36, 128, 64, 2), (17, 4, 4, 128, 128, 1),
+               (2, 4, 4, 1024, 64, 2), (1, 6, 6, 608, 96, 1), (40, 8, 8, 256, 256, 2), (2, 2, 6, 32, 300, 1),
+               (600, 2, 2, 64, 64, 2), (9, 16, 16, 64, 128, 2)]
 
 
 def conv_weights_packed(wt):
@@ -150,6 +158,21 @@ def test_conv_binary_raw_and_fused(n, h, w, ci, co, pool):
     packed2 = fill_i32((n, h // pool, w // pool, (co + 31) // 32), -1)
     P.bnn_conv_binary(xd, n, h, w, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=pool, packed_out=packed2)
     np.testing.assert_array_equal(host_u32(packed2), pack_pm1(s))
+    if pool == 2:
+        packed3 = fill_i32((n, h // 2, w // 2, (co + 31) // 32), -1)
+        P.bnn_conv_binary(xd, n, h, w, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=2, pool_first=1,
+                          packed_out=packed3)
+        np.testing.assert_array_equal(host_u32(packed3),
+                                      pack_pm1(oracle.step(oracle.maxpool2(want), thr, flip)))
+
+
+def test_conv_binary_rejects_too_many_channels():
+    x = fill_i32((1, 4, 4, 40), 0)
+    w = fill_i32((32, 3, 3, 40), 0)
+    out = fill_i32((1, 4, 4, 32), 0)
+    with pytest.raises(P.BnnError) as e:
+        P.bnn_conv_binary(x, 1, 4, 4, 1280, w, 32, preact_out=out)
+    assert e.value.status == 4      # BNN_ERR_UNSUPPORTED
 
 
 def test_conv_binary_closed_form_borders():
@@ -197,6 +220,12 @@ def test_conv_first_int8(n, h, w, ci, co, kh, kw, pad, padv, pool):
                           pool=pool, preact_out=raw2, packed_out=packed)
     np.testing.assert_array_equal(raw2.cpu().numpy(), want)
     np.testing.assert_array_equal(host_u32(packed), pack_pm1(s))
+    if pool == 2:
+        packed3 = fill_i32((n, ho // 2, wo // 2, (co + 31) // 32), -1)
+        P.bnn_conv_first_int8(xd, n, h, w, ci, wd, co, kh, kw, pad, padv, thr=dev(thr), flip=dev(flip),
+                              pool=2, pool_first=1, packed_out=packed3)
+        np.testing.assert_array_equal(host_u32(packed3),
+                                      pack_pm1(oracle.step(oracle.maxpool2(want), thr, flip)))
 
 
 # ------------------------------------------------------------------------- run_model
@@ -244,6 +273,24 @@ def test_run_model_graph_replays(name, batch):
         dm.run(xd, P.RUN_GRAPH)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(dm.logits.cpu().numpy(), logits, err_msg=f"replay {it}")
+
+
+@pytest.mark.parametrize("name,batch", [("small_cnn", 6), ("vgg_small", 3)])
+def test_run_model_paper_layer_order(name, batch):
+    # C -> MP -> S as in the paper's model tables: pool the integers, then step
+    cid, layers, in_shape = W.model_by_name(name)
+    imgs = W.draw_images(W.rng_for(cid, 0, 0), batch, *in_shape)
+    logits, trace = oracle.run_model(layers, imgs, pool_first=True)
+    logits_sp, _ = oracle.run_model(layers, imgs)
+    assert not np.array_equal(logits, logits_sp)          # the two orders differ on flipped channels
+    dm = DeviceModel(layers, batch, in_shape, taps=True, pool_first=True)
+    dm.run(dev(imgs), P.RUN_STREAM)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(dm.logits.cpu().numpy(), logits)
+    for li, (pre, act) in enumerate(trace):
+        if act is not None:
+            want = pack_pm1(act)
+            np.testing.assert_array_equal(host_u32(dm.packed_taps[li]).reshape(want.shape), want)
 
 
 def test_run_model_golden_logits():
