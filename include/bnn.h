@@ -238,6 +238,37 @@ bnn_status bnn_run_model(bnn_model *m, const int8_t *input_dev, int32_t *logits_
 /* Free the host object (and its captured graph).  NULL is allowed. */
 void bnn_model_destroy(bnn_model *m);
 
+/* ------------------------------------------------------------- host-only helpers ----- */
+
+/*
+ * Layer-to-implementation mapping (paper Alg. 1).  Host arrays only, no GPU work.
+ *   cpu_us, gpu_us: [n_batch][n_layers][n_impl], the (CPU time, GPU time) pair that profiling
+ *                   layer l with implementation j at batch-size index b returned; the
+ *                   inference time of the triple is their sum.
+ * For every batch size the implementation with the smallest inference time is chosen per
+ * layer (the first one wins a tie, as a strict '<' scan does) and the minima are summed; the
+ * batch size with the smallest sum wins (first one on a tie).
+ *   best_batch:  out, index of that batch size.
+ *   mapping:     out, [n_layers] implementation indices at that batch size.
+ *   total_us:    out (nullable), its summed inference time.
+ * Errors: NULL, SHAPE (any count < 1, a negative or non-finite time).
+ */
+bnn_status bnn_map_layers(const double *cpu_us, const double *gpu_us, int n_batch, int n_layers,
+                          int n_impl, int *best_batch, int *mapping, double *total_us);
+
+/*
+ * Batch-norm + sign folded into an integer threshold and a flip flag (paper Sec. II-A: the
+ * step layer "can be computed with binary thresholding"; the formula is not given there).
+ * For integer pre-activations x the step output is +1 iff
+ *     gamma * (x - mean) / sqrt(var + eps) + beta > 0 .
+ * With tau = mean - beta * sqrt(var + eps) / gamma this is x > floor(tau) for gamma > 0 and
+ * NOT (x > ceil(tau) - 1) for gamma < 0; gamma == 0 gives a constant (beta > 0).
+ * All arrays are host arrays of n entries; arithmetic is IEEE double; thresholds are clamped
+ * to the int32 range.  Errors: NULL, SHAPE (n < 1, var + eps <= 0, non-finite input).
+ */
+bnn_status bnn_fold_batchnorm(const double *gamma, const double *beta, const double *mean,
+                              const double *var, double eps, int n, int32_t *thr, uint8_t *flip);
+
 #ifdef __cplusplus
 }
 #endif

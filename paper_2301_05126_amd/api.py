@@ -59,6 +59,12 @@ _lib.bnn_run_model.argtypes = [_vp, _vp, _vp, _vp, C.c_size_t, _i, C.POINTER(Lay
                                HOST_LAYER_FN, _vp, _vp]
 _lib.bnn_model_destroy.argtypes = [_vp]
 _lib.bnn_model_destroy.restype = None
+_dp = C.POINTER(C.c_double)
+_lib.bnn_map_layers.argtypes = [_dp, _dp, _i, _i, _i, C.POINTER(_i), C.POINTER(_i), _dp]
+_lib.bnn_fold_batchnorm.argtypes = [_dp, _dp, _dp, _dp, C.c_double, _i, C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_uint8)]
+for _n in ("bnn_map_layers", "bnn_fold_batchnorm"):
+    getattr(_lib, _n).restype = _i
 for _n in ("bnn_pack_bits", "bnn_conv_first_int8", "bnn_conv_binary", "bnn_fc_binary",
            "bnn_threshold_sign_maxpool", "bnn_model_create", "bnn_run_model",
            "bnn_model_num_layers", "bnn_model_num_classes"):
@@ -184,3 +190,33 @@ def bnn_model_destroy(model):
     if model is not None and model.handle:
         _lib.bnn_model_destroy(model.handle)
         model.handle = None
+
+
+def bnn_map_layers(cpu_us, gpu_us):
+    """cpu_us, gpu_us: nested lists / arrays [n_batch][n_layers][n_impl] (host).
+    Returns (best_batch_index, mapping list, total_us)."""
+    import numpy as np
+    c = np.ascontiguousarray(cpu_us, dtype=np.float64)
+    g = np.ascontiguousarray(gpu_us, dtype=np.float64)
+    if c.shape != g.shape or c.ndim != 3:
+        raise ValueError("bnn_map_layers: tables must have the same [batch][layer][impl] shape")
+    nb, nl, ni = c.shape
+    best = C.c_int()
+    mapping = (C.c_int * nl)()
+    total = C.c_double()
+    _check(_lib.bnn_map_layers(c.ctypes.data_as(_dp), g.ctypes.data_as(_dp), nb, nl, ni, C.byref(best),
+                               mapping, C.byref(total)), "bnn_map_layers")
+    return best.value, list(mapping), total.value
+
+
+def bnn_fold_batchnorm(gamma, beta, mean, var, eps):
+    """Host arrays in, (thr int32 array, flip uint8 array) out."""
+    import numpy as np
+    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (gamma, beta, mean, var)]
+    n = arrs[0].shape[0]
+    thr = np.empty(n, dtype=np.int32)
+    flip = np.empty(n, dtype=np.uint8)
+    _check(_lib.bnn_fold_batchnorm(*[a.ctypes.data_as(_dp) for a in arrs], float(eps), n,
+                                   thr.ctypes.data_as(C.POINTER(C.c_int32)),
+                                   flip.ctypes.data_as(C.POINTER(C.c_uint8))), "bnn_fold_batchnorm")
+    return thr, flip

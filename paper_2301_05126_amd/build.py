@@ -12,7 +12,8 @@ LIB = os.path.join(PKG, "libbnn.so")
 
 # (source, extra defines, object name)
 UNITS = [("bnn_api.hip", [], "bnn_api.o"), ("bgemm.hip", [], "bgemm.o"), ("bconv.hip", [], "bconv.o"),
-         ("first_layer.hip", [], "first_layer.o"), ("elementwise.hip", [], "elementwise.o")]
+         ("first_layer.hip", [], "first_layer.o"), ("elementwise.hip", [], "elementwise.o"),
+         ("host_tools.hip", [], "host_tools.o")]
 UNITS += [("bconv_inst.hip", [f"-DBNN_CONV_WPH={w}"], f"bconv_wph{w}.o") for w in (1, 2, 4, 8, 16)]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
