@@ -70,6 +70,15 @@ __device__ __forceinline__ v8i expand_fp4(uint32_t w, uint32_t sgn, uint32_t one
 // Steps (one MFMA K-slice = one word per lane half) per weight chunk, by words per half.
 constexpr int steps_per_chunk(int wph) { return wph == 1 ? 9 : (wph == 2 ? 6 : (wph == 4 ? 12 : 8)); }
 
+// Whether a block keeps all of its weight chunks in LDS at once (64-channel tiles, <= 48 KB).
+constexpr bool weights_resident(int tm, int tn, int wph)
+{
+    const int v = wph >= 4 ? 4 : wph;
+    const int lsb = 2 * steps_per_chunk(wph) + v;
+    const int nchunk = 9 * wph / steps_per_chunk(wph);
+    return tm * tn == 1 && nchunk * 64 * tn * lsb * 4 <= 48 * 1024;
+}
+
 // WPH = words per lane half per tap; the layer's cw words per pixel are zero-padded to 2*WPH.
 template <int TM, int TN, int WPH>
 __global__ __launch_bounds__(256, 2)
@@ -84,11 +93,16 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     constexpr int UPRW = 2 * SPC / V;                  // weight units per row per chunk
     constexpr int STG = (BN * UPRW + 255) / 256;       // weight units per thread per chunk
     constexpr int NVG = SPC / V;                       // V-step groups per chunk
+    // Smallest tile (latency-bound launches, e.g. batch 1): all weight chunks of the block are
+    // loaded up front into their own LDS buffers, so the K loop has no barrier and no global
+    // load latency in it.
+    constexpr bool RES = weights_resident(TM, TN, WPH);
+    constexpr int NBUF = RES ? NCHUNK : 1;
     using vec_t = typename WordVec<V>::type;
 
     extern __shared__ __align__(16) unsigned char smem[];
-    uint32_t *Bs = reinterpret_cast<uint32_t *>(smem);                 // [BN][LSB]
-    uint32_t *Ps = Bs + BN * LSB;                                      // [ni][ph][pw][CWP]
+    uint32_t *Bs = reinterpret_cast<uint32_t *>(smem);                 // [NBUF][BN][LSB]
+    uint32_t *Ps = Bs + NBUF * BN * LSB;                               // [ni][ph][pw][CWP]
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -205,7 +219,27 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
             pb[r] = v;
         }
     };
-    load_w(0);
+    if (RES) {
+        // every chunk: loads of all chunks are in flight together, then one barrier
+        vec_t all[NCHUNK][STG];
+#pragma unroll
+        for (int c = 0; c < NCHUNK; ++c) {
+            load_w(c);
+#pragma unroll
+            for (int r = 0; r < STG; ++r) all[c][r] = pb[r];
+        }
+#pragma unroll
+        for (int c = 0; c < NCHUNK; ++c)
+#pragma unroll
+            for (int r = 0; r < STG; ++r) {
+                const int idx = t + 256 * r;
+                const int row = idx / UPRW, u = idx % UPRW;
+                if (row < BN) *reinterpret_cast<vec_t *>(Bs + (c * BN + row) * LSB + u * V) = all[c][r];
+            }
+        __syncthreads();
+    } else {
+        load_w(0);
+    }
 
     uint32_t sgn = 0x88888888u, one = 0x22222222u;
     asm volatile("" : "+s"(sgn));
@@ -213,15 +247,18 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     constexpr int VPM = (7 * (TM + TN) + TM * TN - 1) / (TM * TN);
 
     for (int c = 0; c < NCHUNK; ++c) {
-        __syncthreads();      // patch staged (first pass) / previous chunk consumed
+        if (!RES) {
+            __syncthreads();      // patch staged (first pass) / previous chunk consumed
 #pragma unroll
-        for (int r = 0; r < STG; ++r) {
-            const int idx = t + 256 * r;
-            const int row = idx / UPRW, u = idx % UPRW;
-            if (row < BN) *reinterpret_cast<vec_t *>(Bs + row * LSB + u * V) = pb[r];
+            for (int r = 0; r < STG; ++r) {
+                const int idx = t + 256 * r;
+                const int row = idx / UPRW, u = idx % UPRW;
+                if (row < BN) *reinterpret_cast<vec_t *>(Bs + row * LSB + u * V) = pb[r];
+            }
+            __syncthreads();
+            if (c + 1 < NCHUNK) load_w(c + 1);
         }
-        __syncthreads();
-        if (c + 1 < NCHUNK) load_w(c + 1);
+        const uint32_t *Bc = RES ? Bs + c * BN * LSB : Bs;
 
         // raw words of V-step group vg: TM pixels' words and TN channels' words
         vec_t ra[2][TM], rb[2][TN];
@@ -234,7 +271,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
             for (int i = 0; i < TM; ++i) ra[slot][i] = *reinterpret_cast<const vec_t *>(Ps + pixoff[i] + aoff);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                rb[slot][j] = *reinterpret_cast<const vec_t *>(Bs + browoff + j * 32 * LSB + vg * V);
+                rb[slot][j] = *reinterpret_cast<const vec_t *>(Bc + browoff + j * 32 * LSB + vg * V);
         };
         load_group(0, 0);
         v8i a[2][TM], b[2][TN];
@@ -305,8 +342,9 @@ size_t smem_bytes(const ConvGeom &g)
 {
     constexpr int V = WPH >= 4 ? 4 : WPH;
     constexpr int LSB = 2 * steps_per_chunk(WPH) + V;
+    constexpr int NBUF = weights_resident(TM, TN, WPH) ? 9 * WPH / steps_per_chunk(WPH) : 1;
     const size_t patch = (size_t)g.ni * ((1 << g.lth) + 2) * ((1 << g.ltw) + 2) * (2 * WPH) * 4;
-    return (size_t)64 * TN * LSB * 4 + patch;
+    return (size_t)NBUF * 64 * TN * LSB * 4 + patch;
 }
 
 template <int TM, int TN, int WPH>

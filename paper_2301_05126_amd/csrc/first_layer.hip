@@ -251,11 +251,7 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
         // input patch as bytes, pad_value outside the image; the slack behind it is zeroed.
         // Loads of four bytes per thread are issued together, then stored.
         {
-#ifdef BNN_X_NOPATCH
-            const int total = 0;
-#else
             const int total = g.ni * ph * pw * g.c_in;
-#endif
             for (int base = 0; base < g.patch_bytes; base += 256 * 4) {
                 int v[4];
 #pragma unroll
@@ -329,7 +325,6 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
             auto getx = [&](int i, int j, int r) { return acc[i][j][r]; };
             const int ch0 = o_blk + grp * 64;
             if (ep.preact) conv_tile_store_preact<2, TN>(getx, wave * 64, ch0, l32, half, pos, ep.preact);
-#ifndef BNN_X_NOEPI
             if (ep.packed) {
                 // select this group's parameters without indexing the register array dynamically
                 StepCols<TN> cur = sc[0];
@@ -338,16 +333,11 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
                     if (grp == q) cur = sc[q];
                 conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, lane, cur, ep.pool, ep.pool_first != 0, Ol);
             }
-#else
-            if (acc[0][0][0] == 0x12345678 && acc[1][1][5] == 77) ep.packed[0] = 1;
-#endif
         }
-#ifndef BNN_X_NOEPI
         if (ep.packed) {
             __syncthreads();
             conv_tile_copy_out<BW>(Ol, 256, o_blk >> 5, pos, ep, t);
         }
-#endif
     }
 }
 
