@@ -102,7 +102,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
 
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t *Bs = reinterpret_cast<uint32_t *>(smem);                 // [NBUF][BN][LSB]
-    uint32_t *Ps = Bs + NBUF * BN * LSB;                               // [ni][ph][pw][CWP]
+    int *Ts = reinterpret_cast<int *>(Bs + NBUF * BN * LSB);           // [BN] thresholds
+    uint32_t *Ps = reinterpret_cast<uint32_t *>(Ts + BN);              // [ni][ph][pw][CWP]
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -123,9 +124,12 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     const int o_blk = co_tile * BN;
     const int pw = tw + 2, ph = th + 2;
 
-    // per-channel step parameters: issued first so their latency hides behind the main loop
-    StepCols<TN> sc;
-    if (ep.packed) sc = load_step_cols<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
+    // per-channel step parameters: fetched first so their latency hides behind the main loop
+    StepWords<TN> sw;
+    if (ep.packed) {
+        sw = load_step_words<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
+        stage_thresholds(ep, o_blk, BN, g.c_out, Ts, t);
+    }
 
     // ---- stage the input patch (halo included; outside the image / beyond cw = zero words).
     // Four units per thread are loaded before any is stored, so the loads overlap.
@@ -295,8 +299,9 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
+                    // weights first: accumulator rows = channels, columns (lanes) = pixels
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        a[cur][i], b[cur][j], acc[i][j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                        b[cur][j], a[cur][i], acc[i][j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
 #pragma unroll
             for (int k = 0; k < TM * TN; ++k) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -317,7 +322,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         // bits -> LDS tile [output pixel][2*TN words] (reusing the weight buffer) -> coalesced stores
         constexpr int BW = 2 * TN;
         __syncthreads();                      // every wave is done with the weight chunk
-        conv_tile_step_to_lds<TM, TN>(getx, wm * TM * 32, wn * TN, BW, lane, sc, ep.pool, ep.pool_first != 0, Bs);
+        conv_tile_step_to_lds<TM, TN>(getx, wm * TM * 32, wn * TN, BW, l32, half, Ts + wn * TN * 32, sw, ep.pool,
+                                      ep.pool_first != 0, Bs);
         __syncthreads();
         conv_tile_copy_out<BW>(Bs, 64 * TM, o_blk >> 5, pos, ep, t);
     }
@@ -344,7 +350,7 @@ size_t smem_bytes(const ConvGeom &g)
     constexpr int LSB = 2 * steps_per_chunk(WPH) + V;
     constexpr int NBUF = weights_resident(TM, TN, WPH) ? 9 * WPH / steps_per_chunk(WPH) : 1;
     const size_t patch = (size_t)g.ni * ((1 << g.lth) + 2) * ((1 << g.ltw) + 2) * (2 * WPH) * 4;
-    return (size_t)NBUF * 64 * TN * LSB * 4 + patch;
+    return (size_t)NBUF * 64 * TN * LSB * 4 + 64 * TN * 4 + patch;
 }
 
 template <int TM, int TN, int WPH>

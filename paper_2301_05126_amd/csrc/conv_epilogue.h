@@ -1,12 +1,19 @@
 // Epilogue shared by the convolution kernels that run on the matrix cores.
 //
-// A wave holds TM x TN accumulator tiles of 32 x 32.  GEMM rows are pixels numbered
-// window-major inside the block (row = 4 * window + 2*dy + dx, windows enumerated x-fastest
-// over the spatial tile, then over the block's images); columns are output channels.
-// Accumulator register r of lane (l32, half) is row 8*(r/4) + 4*half + r%4 of its tile and
-// column l32, so the four registers r = 4a..4a+3 of a lane are one 2x2 window: max-pool
-// after the step layer (paper Sec. II-A) is an OR of four predicates, and a wave-wide ballot
-// of a predicate is the packed word of 32 consecutive channels (lower / upper 32 lanes).
+// A wave holds TM x TN accumulator tiles of 32 x 32 computed as (weights) x (pixels)^T: the
+// weight operand is the MFMA's first matrix, so accumulator register r of lane (l32, half)
+// is output channel 8*(r/4) + 4*half + r%4 of the tile and pixel l32.  A lane therefore
+// owns 16 channels of one pixel:
+//   - the step layer (paper Sec. II-A) is, per register, a subtract and a funnel shift that
+//     appends the sign bit of (thr - x) to a 16-bit code (x > thr  <=>  thr - x < 0);
+//   - the four nibbles of the code are spread to their channel positions, the two lane
+//     halves are merged, the per-channel flip word is xor-ed in: one packed word per pixel;
+//   - pixels are numbered window-major inside the block (GEMM row = 4 * window + 2*dy + dx,
+//     windows x-fastest over the spatial tile, then over the block's images), so a 2x2 pool
+//     window is four neighbouring lanes: max-pool after the step is an OR over a lane quad,
+//     max-pool before the step a max over the quad (DPP quad permutes).
+// Thresholds sit in LDS (clamped to +-2^30, which no sum can reach, so thr - x never
+// overflows); words go to an LDS output tile and leave as one vector store per pixel.
 #ifndef BNN_CONV_EPILOGUE_H
 #define BNN_CONV_EPILOGUE_H
 
@@ -22,133 +29,130 @@ struct TilePos {
     int img0, y0, x0;        // first image and tile origin of this block
 };
 
+// Position of GEMM row `row` (window-major) inside the block's tile.
+__device__ __forceinline__ void row_to_pixel(int row, const TilePos &p, int &img, int &y, int &x)
+{
+    const int lhw = p.ltw - 1, lhh = p.lth - 1;
+    const int wq = row >> 2, sub = row & 3;
+    const int wx = wq & ((1 << lhw) - 1);
+    const int wy = (wq >> lhw) & ((1 << lhh) - 1);
+    img = p.img0 + (wq >> (lhw + lhh));
+    y = p.y0 + 2 * wy + (sub >> 1);
+    x = p.x0 + 2 * wx + (sub & 1);
+}
+
 // Raw int32 output of one wave's tiles (debug / "no step" path).
-// getx(i, j, r) returns the integer pre-activation held in accumulator (i, j, r).
+// getx(i, j, r): pre-activation of pixel tile i, channel tile j, register r.
 // row0 = first GEMM row of this wave inside the block, ch0 = first channel of this wave.
 template <int TM, int TN, typename GetX>
 __device__ __forceinline__ void conv_tile_store_preact(GetX getx, int row0, int ch0, int l32, int half,
                                                        const TilePos &p, int32_t *preact)
 {
-    const int lhw = p.ltw - 1, lhh = p.lth - 1;
-    const int col0 = ch0 + l32;
+    const bool vec_ok = (p.c_out & 3) == 0;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        int img, y, x;
+        row_to_pixel(row0 + i * 32 + l32, p, img, y, x);
+        if (img >= p.n || y >= p.h || x >= p.w) continue;
+        int32_t *dst = preact + (((int64_t)img * p.h + y) * p.w + x) * p.c_out;
 #pragma unroll
-        for (int a4 = 0; a4 < 4; ++a4) {
-            const int wq = (row0 + i * 32) / 4 + 2 * a4 + half;
-            const int wx = wq & ((1 << lhw) - 1);
-            const int wy = (wq >> lhw) & ((1 << lhh) - 1);
-            const int img = p.img0 + (wq >> (lhw + lhh));
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int sub = 0; sub < 4; ++sub) {
-                const int y = p.y0 + 2 * wy + (sub >> 1), x = p.x0 + 2 * wx + (sub & 1);
-                if (img < p.n && y < p.h && x < p.w) {
-                    int32_t *dst = preact + (((int64_t)img * p.h + y) * p.w + x) * p.c_out;
+            for (int q = 0; q < 4; ++q) {
+                const int c = ch0 + j * 32 + q * 8 + half * 4;
+                if (vec_ok && c + 4 <= p.c_out) {
+                    *reinterpret_cast<int4 *>(dst + c) =
+                        make_int4(getx(i, j, q * 4), getx(i, j, q * 4 + 1), getx(i, j, q * 4 + 2), getx(i, j, q * 4 + 3));
+                } else {
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const int col = col0 + j * 32;
-                        if (col < p.c_out) dst[col] = getx(i, j, a4 * 4 + sub);
-                    }
+                    for (int k = 0; k < 4; ++k)
+                        if (c + k < p.c_out) dst[c + k] = getx(i, j, q * 4 + k);
                 }
             }
-        }
+    }
 }
 
-// v_writelane_b32: put a wave-uniform value into lane `LANE` of a register.
-template <int LANE>
-__device__ __forceinline__ int write_lane(int old, unsigned value)
+// Block-cooperative: thresholds of the block's `nch` channels (first one ch_blk0) into LDS,
+// clamped to +-2^30; channels beyond c_out get 0.  Followed by a barrier before use.
+__device__ __forceinline__ void stage_thresholds(const EpiArgs &ep, int ch_blk0, int nch, int c_out,
+                                                 int *thr_lds, int t)
 {
-    const unsigned uniform = __builtin_amdgcn_readfirstlane(value);   // pins the value to a scalar register
-    asm("v_writelane_b32 %0, %1, %2" : "+v"(old) : "s"(uniform), "n"(LANE));
-    return old;
+    for (int c = t; c < nch; c += 256) {
+        int v = 0;
+        if (ch_blk0 + c < c_out) v = ep.thr[ch_blk0 + c];
+        v = v > (1 << 30) ? (1 << 30) : (v < -(1 << 30) ? -(1 << 30) : v);
+        thr_lds[c] = v;
+    }
 }
 
-// Per-column step parameters of one lane: the threshold of its channel in each of the wave's
-// TN tiles and two flags (bit 0: comparison flipped, bit 1: channel exists).  Loaded once
-// per block; kept in vector registers, the wave-wide masks are rebuilt where they are used.
+// Per 32-channel tile of a wave: packed words of the flipped / existing channels.
 template <int TN>
-struct StepCols {
-    int thr[TN];
-    int flags[TN];
+struct StepWords {
+    unsigned flipw[TN], okw[TN];
 };
 
 template <int TN>
-__device__ __forceinline__ StepCols<TN> load_step_cols(const EpiArgs &ep, int ch0, int l32, int c_out)
+__device__ __forceinline__ StepWords<TN> load_step_words(const EpiArgs &ep, int ch0, int l32, int c_out)
 {
-    StepCols<TN> sc;
+    StepWords<TN> sw;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = ch0 + j * 32 + l32;
         const bool cok = col < c_out;
-        sc.thr[j] = cok ? ep.thr[col] : 0;
-        sc.flags[j] = (cok ? 2 : 0) | ((cok && ep.flip && ep.flip[col]) ? 1 : 0);
+        sw.flipw[j] = (unsigned)__ballot(cok && ep.flip && ep.flip[col]);      // lanes 0..31 = channels
+        sw.okw[j] = (unsigned)__ballot(cok);
     }
-    return sc;
+    return sw;
 }
 
-// One parked word pair: mask halves -> lanes K and 32 + K of `parked`.
-template <int K>
-__device__ __forceinline__ int park_pair(int parked, unsigned long long m)
-{
-    parked = write_lane<K>(parked, (unsigned)m);
-    parked = write_lane<32 + K>(parked, (unsigned)(m >> 32));
-    return parked;
-}
+// quad-lane exchanges (DPP quad_perm [1,0,3,2] and [2,3,0,1])
+__device__ __forceinline__ int quad_xor1(int v) { return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false); }
+__device__ __forceinline__ int quad_xor2(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false); }
 
-template <int TM, int TN, typename GetX, int... R>
-__device__ __forceinline__ int park_rows(GetX getx, int i, int j, int thr, unsigned long long fm,
-                                         unsigned long long om, std::integer_sequence<int, R...>)
-{
-    int parked = 0;
-    ((parked = park_pair<R>(parked, (__ballot(getx(i, j, R) > thr) ^ fm) & om)), ...);
-    return parked;
-}
-
-template <int TM, int TN, typename GetX, int... W>
-__device__ __forceinline__ int park_windows(GetX getx, int j, int thr, unsigned long long fm,
-                                            unsigned long long om, bool pool_first,
-                                            std::integer_sequence<int, W...>)
-{
-    int parked = 0;
-    auto window = [&](int i, int a4) {
-        unsigned long long m = 0;
-        if (pool_first) {
-            // max of the four pre-activations, then one comparison
-            int x = getx(i, j, a4 * 4);
-#pragma unroll
-            for (int sub = 1; sub < 4; ++sub) x = max(x, getx(i, j, a4 * 4 + sub));
-            m = __ballot(x > thr) ^ fm;
-        } else {
-#pragma unroll
-            for (int sub = 0; sub < 4; ++sub) m |= __ballot(getx(i, j, a4 * 4 + sub) > thr) ^ fm;
-        }
-        return m & om;
-    };
-    ((parked = park_pair<W>(parked, window(W / 4, W % 4))), ...);
-    return parked;
-}
-
+// Step (+ pool) of one wave's tiles into the block's LDS output tile.
+// out_lds is [output pixel of the block][bw words]; an output pixel is a GEMM row (pool 1) or
+// a window (pool 2).  word0 = index, inside the block's bw words, of this wave's first 32
+// channels; thr_wave = LDS thresholds of this wave's first channel.
 template <int TM, int TN, typename GetX>
-__device__ __forceinline__ void conv_tile_step_to_lds(GetX getx, int row0, int word0, int bw, int lane,
-                                                      const StepCols<TN> &sc, int pool, bool pool_first,
-                                                      uint32_t *out_lds)
+__device__ __forceinline__ void conv_tile_step_to_lds(GetX getx, int row0, int word0, int bw, int l32, int half,
+                                                      const int *thr_wave, const StepWords<TN> &sw, int pool,
+                                                      bool pool_first, uint32_t *out_lds)
 {
-    const int k = lane & 31, hf = lane >> 5;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const unsigned long long fm = __ballot((sc.flags[j] & 1) != 0), om = __ballot((sc.flags[j] & 2) != 0);
-        const int thr = sc.thr[j];
-        if (pool == 2) {
-            // window W = 4i + a4 of this wave -> lanes W (lower rows) and 32 + W
-            const int parked = park_windows<TM, TN>(getx, j, thr, fm, om, pool_first, std::make_integer_sequence<int, TM * 4>{});
-            // lane (k, hf) holds window (row0/4) + 8*(k/4) + 2*(k%4) + hf
-            if (k < TM * 4) out_lds[((row0 >> 2) + (k >> 2) * 8 + (k & 3) * 2 + hf) * bw + word0 + j] = (uint32_t)parked;
-        } else {
+        // this lane's 16 thresholds: channels 8q + 4*half + (0..3), q = 0..3
+        int thr[16];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int parked = park_rows<TM, TN>(getx, i, j, thr, fm, om, std::make_integer_sequence<int, 16>{});
-                // lane (k, hf), k < 16, holds row row0 + 32i + 8*(k/4) + 4*hf + k%4
-                if (k < 16) out_lds[(row0 + i * 32 + (k >> 2) * 8 + hf * 4 + (k & 3)) * bw + word0 + j] = (uint32_t)parked;
+        for (int q = 0; q < 4; ++q) {
+            const int4 t4 = *reinterpret_cast<const int4 *>(thr_wave + j * 32 + q * 8 + half * 4);
+            thr[q * 4] = t4.x; thr[q * 4 + 1] = t4.y; thr[q * 4 + 2] = t4.z; thr[q * 4 + 3] = t4.w;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            unsigned code = 0;                       // bit r = (x_r > thr_r)
+#pragma unroll
+            for (int r = 15; r >= 0; --r) {
+                int x = getx(i, j, r);
+                if (pool == 2 && pool_first) {       // max over the window's four pixels first
+                    x = max(x, quad_xor1(x));
+                    x = max(x, quad_xor2(x));
+                }
+                code = __builtin_amdgcn_alignbit(code, (unsigned)(thr[r] - x), 31);
+            }
+            // nibble q of the code -> channels 8q + 4*half .. +3
+            unsigned w = (code & 0xFu) | ((code & 0xF0u) << 4) | ((code & 0xF00u) << 8) | ((code & 0xF000u) << 12);
+            w <<= 4 * half;
+            w |= (unsigned)__shfl_xor((int)w, 32);
+            w = (w ^ sw.flipw[j]) & sw.okw[j];
+            const int row = row0 + i * 32 + l32;
+            if (pool == 2) {
+                if (!pool_first) {                   // OR over the window
+                    w |= (unsigned)quad_xor1((int)w);
+                    w |= (unsigned)quad_xor2((int)w);
+                }
+                if (half == 0 && (l32 & 3) == 0) out_lds[(row >> 2) * bw + word0 + j] = w;
+            } else {
+                if (half == 0) out_lds[row * bw + word0 + j] = w;
             }
         }
     }

@@ -176,7 +176,8 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
     constexpr int BW = 2 * NG;                                  // packed output words per pixel
     unsigned char *Wl = smem;                                   // [64*NG][ws]
     uint32_t *Ol = reinterpret_cast<uint32_t *>(smem + 64 * NG * ws);      // [256][BW]
-    unsigned char *Pl = smem + 64 * NG * ws + 256 * BW * 4;     // [ni][ph][pw][c_in] + slack
+    int *Tl = reinterpret_cast<int *>(smem + 64 * NG * ws + 256 * BW * 4);  // [64*NG] thresholds
+    unsigned char *Pl = smem + 64 * NG * ws + 256 * BW * 4 + 64 * NG * 4;   // [ni][ph][pw][c_in] + slack
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -232,11 +233,13 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
     const int nsteps = g.kp >> 5;
     const unsigned *P32 = reinterpret_cast<const unsigned *>(Pl);
 
-    // per-channel step parameters, loaded once per block
-    StepCols<TN> sc[NG];
+    // per-channel step parameters, fetched once per block (the first barrier of the tile
+    // loop publishes the thresholds)
+    StepWords<TN> sw[NG];
     if (ep.packed) {
 #pragma unroll
-        for (int grp = 0; grp < NG; ++grp) sc[grp] = load_step_cols<TN>(ep, o_blk + grp * 64, l32, g.c_out);
+        for (int grp = 0; grp < NG; ++grp) sw[grp] = load_step_words<TN>(ep, o_blk + grp * 64, l32, g.c_out);
+        stage_thresholds(ep, o_blk, 64 * NG, g.c_out, Tl, t);
     }
 
     // ---- persistent loop over (image group, tile) work items
@@ -319,19 +322,20 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
                     const v4i b = *reinterpret_cast<const v4i *>(Wl + ((grp * TN + j) * 32 + l32) * ws + ks * 32 + half * 16);
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[ks][i], b, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a[ks][i], acc[i][j], 0, 0, 0);   // rows = channels
                 }
             }
             auto getx = [&](int i, int j, int r) { return acc[i][j][r]; };
             const int ch0 = o_blk + grp * 64;
             if (ep.preact) conv_tile_store_preact<2, TN>(getx, wave * 64, ch0, l32, half, pos, ep.preact);
             if (ep.packed) {
-                // select this group's parameters without indexing the register array dynamically
-                StepCols<TN> cur = sc[0];
+                // select this group's words without indexing the register array dynamically
+                StepWords<TN> cur = sw[0];
 #pragma unroll
                 for (int q = 1; q < NG; ++q)
-                    if (grp == q) cur = sc[q];
-                conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, lane, cur, ep.pool, ep.pool_first != 0, Ol);
+                    if (grp == q) cur = sw[q];
+                conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, l32, half, Tl + grp * 64, cur, ep.pool,
+                                             ep.pool_first != 0, Ol);
             }
         }
         if (ep.packed) {
@@ -397,7 +401,7 @@ template <int NG>
 bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, const EpiArgs &ep, hipStream_t s)
 {
     g.n_co_tiles = (g.c_out + 64 * NG - 1) / (64 * NG);
-    const size_t smem = (size_t)64 * NG * (g.kp + 16) + 256 * 2 * NG * 4 + g.patch_bytes;
+    const size_t smem = (size_t)64 * NG * (g.kp + 16) + 256 * 2 * NG * 4 + 64 * NG * 4 + g.patch_bytes;
     const int64_t items = (int64_t)g.tiles_x * g.tiles_y * ((g.n + g.ni - 1) / g.ni);
     if (smem > 64 * 1024 || items > 0x7fffffffLL || g.n_co_tiles > 65535) return BNN_ERR_UNSUPPORTED;
     g.n_items = (int)items;
