@@ -12,7 +12,7 @@
 // last word) count as matches, a constant that the epilogue subtracts.
 //
 //   bgemm_mfma<TM,TN>  block = 2x2 waves, wave tile (32*TM) x (32*TN), K streamed through
-//                      LDS as packed words in 16-word chunks.
+//                      LDS as packed words in chunks of 16 .. 64 words.
 //   bgemv_rows         m <= 8: bandwidth-bound, xor + popcount on the VALU, four output rows of
 //                      B per wave, halving-butterfly reduction over the 64 lanes.
 // Both end in the same epilogue: optional int32 store, optional threshold/flip/bit-pack.
@@ -25,9 +25,9 @@ namespace {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int KC = 16;        // packed k-words per LDS chunk (512 bits of K)
-constexpr int LS = KC + 4;    // LDS row stride in words; LS/4 odd -> 16-byte reads of
-                              // consecutive rows fall into distinct bank groups
+// Packed k-words per LDS chunk: small tiles take long chunks (fewer barriers per MFMA, their
+// launches are latency-bound), the 256 x 256 tile short ones (registers).
+constexpr int chunk_words(int tm, int tn) { return tm * tn >= 16 ? 16 : (tm * tn >= 4 ? 32 : 64); }
 
 template <int VEC>
 __device__ __forceinline__ uint4 load_row_words(const uint32_t *__restrict__ base, int64_t row,
@@ -76,6 +76,11 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
                                                       int Kw, int K, int nbn, EpiArgs ep)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;     // 2 x 2 waves
+    constexpr int KC = chunk_words(TM, TN);
+    constexpr int LS = KC + 4;    // LDS row stride in words; LS/4 odd -> 16-byte reads of
+                                  // consecutive rows fall into distinct bank groups
+    constexpr int UPR = KC / 4, SA = BM * UPR / 256, SB = BN * UPR / 256;   // staging units
+    constexpr int NG = KC / 8, NST = KC / 2;      // 8-word groups and MFMA steps per chunk
     __shared__ __align__(16) uint32_t As[BM * LS];
     __shared__ __align__(16) uint32_t Bs[BN * LS];
 
@@ -98,18 +103,18 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // staging: a chunk of a tile is (rows x 4) 16-byte units; TM units of A, TN of B per thread
-    uint4 pa[TM], pb[TN];
+    // staging: a chunk of a tile is (rows x UPR) 16-byte units; SA units of A, SB of B per thread
+    uint4 pa[SA], pb[SB];
     auto prefetch = [&](int k0) {
 #pragma unroll
-        for (int r = 0; r < TM; ++r) {
+        for (int r = 0; r < SA; ++r) {
             const int idx = t + 256 * r;
-            pa[r] = load_row_words<VEC>(A, m0 + (idx >> 2), M, Kw, k0 + (idx & 3) * 4);
+            pa[r] = load_row_words<VEC>(A, m0 + idx / UPR, M, Kw, k0 + (idx % UPR) * 4);
         }
 #pragma unroll
-        for (int r = 0; r < TN; ++r) {
+        for (int r = 0; r < SB; ++r) {
             const int idx = t + 256 * r;
-            pb[r] = load_row_words<VEC>(B, n0 + (idx >> 2), N, Kw, k0 + (idx & 3) * 4);
+            pb[r] = load_row_words<VEC>(B, n0 + idx / UPR, N, Kw, k0 + (idx % UPR) * 4);
         }
     };
     prefetch(0);
@@ -126,23 +131,23 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
     for (int kc = 0; kc < nchunks; ++kc) {
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < TM; ++r) {
+        for (int r = 0; r < SA; ++r) {
             const int idx = t + 256 * r;
-            *reinterpret_cast<uint4 *>(As + (idx >> 2) * LS + (idx & 3) * 4) = pa[r];
+            *reinterpret_cast<uint4 *>(As + (idx / UPR) * LS + (idx % UPR) * 4) = pa[r];
         }
 #pragma unroll
-        for (int r = 0; r < TN; ++r) {
+        for (int r = 0; r < SB; ++r) {
             const int idx = t + 256 * r;
-            *reinterpret_cast<uint4 *>(Bs + (idx >> 2) * LS + (idx & 3) * 4) = pb[r];
+            *reinterpret_cast<uint4 *>(Bs + (idx / UPR) * LS + (idx % UPR) * 4) = pb[r];
         }
         __syncthreads();
         if (kc + 1 < nchunks) prefetch((kc + 1) * KC);
 
-        // a chunk = two groups of 8 words; lane half h owns words [8g + 4h, 8g + 4h + 4).
+        // a chunk = NG groups of 8 words; lane half h owns words [8g + 4h, 8g + 4h + 4).
         // Operands of step s+1 are expanded on the VALU while the matrix core runs step s.
-        uint4 wa[2][TM], wb[2][TN];
+        uint4 wa[NG][TM], wb[NG][TN];
 #pragma unroll
-        for (int g = 0; g < 2; ++g) {
+        for (int g = 0; g < NG; ++g) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) wa[g][i] = *reinterpret_cast<const uint4 *>(a_rd + i * 32 * LS + g * 8);
 #pragma unroll
@@ -154,9 +159,9 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
 #pragma unroll
         for (int j = 0; j < TN; ++j) b[0][j] = expand_fp4(wb[0][j].x, sgn, one);
 #pragma unroll
-        for (int st = 0; st < 8; ++st) {
+        for (int st = 0; st < NST; ++st) {
             const int cur = st & 1, nxt = cur ^ 1;
-            if (st + 1 < 8) {
+            if (st + 1 < NST) {
                 const int g = (st + 1) >> 2, q = (st + 1) & 3;
 #pragma unroll
                 for (int i = 0; i < TM; ++i) a[nxt][i] = expand_fp4(word_of(wa[g][i], q), sgn, one);

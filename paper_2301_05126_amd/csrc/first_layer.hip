@@ -153,7 +153,7 @@ struct FirstGeomM {
     int lth, ltw, ni, tiles_x, tiles_y, n_co_tiles, n_items;
     int sl, slp, kp;            // bytes of one kernel row, padded to 16, and padded K (multiple of 32)
     int patch_bytes;
-    unsigned mg_cin, mg_pw, mg_ph;   // ceil(2^32 / d) for d = c_in, patch width, patch height
+    unsigned mg_cin, mg_pw, mg_ph, mg_kh;   // ceil(2^32 / d) for d = c_in, patch width / height, kh
 };
 
 // floor(n / d) for n, d < 2^16 with mg = ceil(2^32 / d) (mg == 0 stands for d == 1): one v_mul_hi_u32.
@@ -188,32 +188,35 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
     const int o_blk = co_tile * 64 * NG;
     const int pw = tw + g.kw - 1, ph = th + g.kh - 1;
 
-    // ---- weights of this block's channels in the K-padded layout, staged once per block:
-    // zero the tile, then scatter the source bytes (independent loads, several in flight)
+    // ---- weights of this block's channels in the K-padded layout, staged once per block.
+    // One thread per (channel, kernel row): its sl source bytes are contiguous in memory and
+    // land at the start of a slp-byte slot whose rest is zero; loads of a slot are issued
+    // together.  The K padding behind the last kernel row is zeroed separately.
     {
         const int k_total = g.kh * g.sl;
         const int nrow = 64 * NG;
-        for (int idx = t; idx < nrow * (ws >> 2); idx += 256) reinterpret_cast<unsigned *>(Wl)[idx] = 0u;
-        __syncthreads();
-        const int rows_here = min(nrow, g.c_out - o_blk);
-        const int total = rows_here * k_total;
-        const int8_t *wsrc = wt + (int64_t)o_blk * k_total;       // rows are contiguous in memory
-        for (int base = 0; base < total; base += 256 * 8) {
-            int8_t v[8];
+        for (int pair = t; pair < nrow * g.kh; pair += 256) {
+            const int row = div_magic(pair, g.mg_kh), ti = pair - row * g.kh;
+            const int o = o_blk + row;
+            const int8_t *src = wt + (int64_t)o * k_total + ti * g.sl;
+            unsigned char *dst = Wl + row * ws + ti * g.slp;
+            const bool ok = o < g.c_out;
+            for (int b0 = 0; b0 < g.slp; b0 += 16) {
+                int8_t v[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = base + u * 256 + t;
-                v[u] = idx < total ? wsrc[idx] : (int8_t)0;
+                for (int q = 0; q < 16; ++q) v[q] = (ok && b0 + q < g.sl) ? src[b0 + q] : (int8_t)0;
+                uint4 w4;
+                w4.x = (uint8_t)v[0] | ((uint8_t)v[1] << 8) | ((uint8_t)v[2] << 16) | ((unsigned)(uint8_t)v[3] << 24);
+                w4.y = (uint8_t)v[4] | ((uint8_t)v[5] << 8) | ((uint8_t)v[6] << 16) | ((unsigned)(uint8_t)v[7] << 24);
+                w4.z = (uint8_t)v[8] | ((uint8_t)v[9] << 8) | ((uint8_t)v[10] << 16) | ((unsigned)(uint8_t)v[11] << 24);
+                w4.w = (uint8_t)v[12] | ((uint8_t)v[13] << 8) | ((uint8_t)v[14] << 16) | ((unsigned)(uint8_t)v[15] << 24);
+                *reinterpret_cast<uint4 *>(dst + b0) = w4;
             }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = base + u * 256 + t;
-                if (idx < total) {
-                    const int row = idx / k_total, kk = idx - row * k_total;
-                    const int ti = kk / g.sl, off = kk - ti * g.sl;
-                    Wl[row * ws + ti * g.slp + off] = (unsigned char)v[u];
-                }
-            }
+        }
+        const int tail0 = g.kh * g.slp, tail = g.kp - tail0;      // multiple of 16 bytes
+        for (int idx = t; idx < nrow * (tail >> 4); idx += 256) {
+            const int row = idx / (tail >> 4), u = idx - row * (tail >> 4);
+            *reinterpret_cast<uint4 *>(Wl + row * ws + tail0 + u * 16) = make_uint4(0u, 0u, 0u, 0u);
         }
     }
 
@@ -447,6 +450,7 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
         g.mg_cin = magic(c_in);
         g.mg_pw = magic((1 << g.ltw) + kw - 1);
         g.mg_ph = magic((1 << g.lth) + kh - 1);
+        g.mg_kh = magic(kh);
         if (g.kp <= 128 && pbytes <= 24 * 1024) {
             const bnn_status st = (c_out > 64) ? launch_first_mfma<2>(in, wt, g, ep, s)
                                                : launch_first_mfma<1>(in, wt, g, ep, s);
