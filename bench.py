@@ -146,7 +146,8 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom_name)
+            entry = json.load(open(tpath)).get(args.workload, {}).get(dom_name)
+            traffic = entry["hbm_bytes_per_launch"] if entry else None
         except Exception:
             traffic = None
     roofline = {
