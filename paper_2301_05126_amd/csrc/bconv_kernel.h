@@ -6,19 +6,21 @@
 // fall outside the image read zero words, i.e. -1 activations, so every output sums exactly
 // K = 9*c_in products.
 //
-// A block of 4 waves (2 x 2) computes (64*TM pixels) x (64*TN output channels).  The pixels
-// are `ni` images x (th x tw) spatial tile whose input patch, halo included, is staged once
+// A block of 4 waves (2 x 2) computes (64*TM pixels) x (64*TN output channels) per pixel
+// tile and is persistent: it keeps one channel tile and walks over pixel tiles.  The pixels
+// of a tile are `ni` images x (th x tw) spatial tile whose input patch, halo included, sits
 // in LDS as packed words; the nine taps are read from it with shifted addresses.  Weights
-// stream through LDS in chunks of a few taps.  Every 32-bit word of either operand is
-// expanded in registers into 32 FP4 values +-1.0 and multiplied by
-// v_mfma_scale_f32_32x32x64_f8f6f4; sums stay below 2^24 so the FP32 accumulators are exact.
-// Within one MFMA the lower 32 lanes supply the first half of a pixel's channel words and
-// the upper 32 lanes the second half (same split on the weight side).
+// are resident in LDS when they fit, else they stream through it in chunks of a few taps.
+// Every 32-bit word of either operand is expanded in registers into 32 FP4 values +-1.0 and
+// multiplied by v_mfma_f32_32x32x64_f8f6f4 (no block scales); all sums are multiples of 1/2
+// far below 2^23, so the FP32 accumulators are exact.  Within one MFMA the lower 32 lanes
+// supply the first half of a pixel's channel words and the upper 32 lanes the second half
+// (same split on the weight side).
 //
-// Pixels are numbered window-major (four consecutive rows of the implicit GEMM are one 2x2
-// window), which puts a pool window into four accumulator registers of one lane: max-pool
-// after the sign is an OR of four predicate bits.  A wave-wide ballot of the predicate is the
-// packed output word (32 lanes = 32 consecutive channels).
+// The weights are the MFMA's first operand, so a lane owns 16 channels of one pixel, and
+// pixels are numbered window-major (four consecutive rows of the implicit GEMM are one 2x2
+// window = one lane quad); the step and pool layers fused behind the sums are described in
+// conv_epilogue.h.
 #ifndef BNN_BCONV_KERNEL_H
 #define BNN_BCONV_KERNEL_H
 #include "bnn_internal.h"
@@ -32,14 +34,6 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int MAX_SMEM = 64 * 1024;
-
-struct ConvGeom {
-    int n, h, w, cw;             // input: images, height, width, words per pixel
-    int c_out, k_bits;           // outputs, K = 9*c_in
-    int lth, ltw;                // log2 of the spatial tile height / width (both >= 1)
-    int ni;                      // images per block; ni * th * tw == pixels per block
-    int tiles_x, tiles_y, n_co_tiles;
-};
 
 template <int V> struct WordVec;
 template <> struct WordVec<4> { using type = uint4; };
@@ -67,24 +61,77 @@ __device__ __forceinline__ v8i expand_fp4(uint32_t w, uint32_t sgn, uint32_t one
     return r;
 }
 
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// Buffer resource over `bytes` bytes at `base` (raw buffer, offsets past the end read zeros).
+__device__ __forceinline__ v4i make_raw_rsrc(const void *base, unsigned bytes)
+{
+    const unsigned long long a = (unsigned long long)base;
+    v4i r;
+    r[0] = (int)(unsigned)a;
+    r[1] = (int)(unsigned)((a >> 32) & 0xffffu);       // stride 0
+    r[2] = (int)bytes;
+    r[3] = 0x00020000;
+    return r;
+}
+
+// One wave-wide copy global -> LDS without touching vector registers: lane l's 16 (or 4)
+// bytes at byte offset voff of the buffer land at LDS byte address lds_base + 16*l (4*l).
+// Written as inline assembly so that the compiler does not serialise the transfer against
+// the LDS reads of the tile being multiplied; completion is awaited explicitly
+// (s_waitcnt vmcnt(0)) before the barrier that publishes the buffer.  lds_base is wave-uniform.
+__device__ __forceinline__ void lds_dma16(v4i rsrc, unsigned lds_base, unsigned voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ void lds_dma4(v4i rsrc, unsigned lds_base, unsigned voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
+}
+
 // Steps (one MFMA K-slice = one word per lane half) per weight chunk, by words per half.
 constexpr int steps_per_chunk(int wph) { return wph == 1 ? 9 : (wph == 2 ? 6 : (wph == 4 ? 12 : 8)); }
 
-// Whether a block keeps all of its weight chunks in LDS at once (64-channel tiles, <= 48 KB).
+// Whether a block keeps all of its weight chunks in LDS at once: up to 24 KB for any tile
+// (C_in <= 128), up to 48 KB for the 64-channel tile.
 constexpr bool weights_resident(int tm, int tn, int wph)
 {
     const int v = wph >= 4 ? 4 : wph;
     const int lsb = 2 * steps_per_chunk(wph) + v;
     const int nchunk = 9 * wph / steps_per_chunk(wph);
-    return tm * tn == 1 && nchunk * 64 * tn * lsb * 4 <= 48 * 1024;
+    const int bytes = nchunk * 64 * tn * lsb * 4;
+    return bytes <= 24 * 1024 || (tm * tn == 1 && bytes <= 48 * 1024);
 }
 
+struct ConvGeom {
+    int n, h, w, cw;             // input: images, height, width, words per pixel
+    int c_out, k_bits;           // outputs, K = 9*c_in
+    int lth, ltw;                // log2 of the spatial tile height / width (both >= 1)
+    int ni;                      // images per pixel tile; ni * th * tw == pixels per block
+    int tiles_x, tiles_y, n_co_tiles;
+    int n_ptiles;                // pixel tiles in the layer
+    int slots;                   // blocks per channel tile = pixel tiles in flight
+    int patch_words;             // LDS words of one patch buffer (rounded up)
+    int dbuf;                    // 1: two patch buffers, the next tile's patch is fetched during the MFMAs
+    unsigned mg_pw, mg_ph;       // ceil(2^32 / d) for d = patch width, patch height (staging index math)
+};
+
 // WPH = words per lane half per tap; the layer's cw words per pixel are zero-padded to 2*WPH.
+//
+// Blocks are persistent: block b owns channel tile b % n_co_tiles for its whole life (so
+// thresholds, and the weights when they are resident, are fetched once) and walks the pixel
+// tiles slot, slot + slots, ...  The input patch of a tile goes global -> LDS without passing
+// through registers (buffer_load ... lds; lanes outside the image or beyond the last image
+// address past the buffer's end and deliver zeros, i.e. -1 padding); with two patch buffers
+// the next tile's patch is in flight while the current tile is multiplied.
 template <int TM, int TN, int WPH>
 __global__ __launch_bounds__(256, 2)
 void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt, ConvGeom g, EpiArgs ep)
 {
     constexpr int BN = 64 * TN;
+    constexpr int BW = 2 * TN;                         // packed output words per pixel of a block
     constexpr int CWP = 2 * WPH;                       // padded words per pixel
     constexpr int V = WPH >= 4 ? 4 : WPH;              // words per LDS access
     constexpr int SPC = steps_per_chunk(WPH);
@@ -93,17 +140,15 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     constexpr int UPRW = 2 * SPC / V;                  // weight units per row per chunk
     constexpr int STG = (BN * UPRW + 255) / 256;       // weight units per thread per chunk
     constexpr int NVG = SPC / V;                       // V-step groups per chunk
-    // Smallest tile (latency-bound launches, e.g. batch 1): all weight chunks of the block are
-    // loaded up front into their own LDS buffers, so the K loop has no barrier and no global
-    // load latency in it.
     constexpr bool RES = weights_resident(TM, TN, WPH);
     constexpr int NBUF = RES ? NCHUNK : 1;
     using vec_t = typename WordVec<V>::type;
 
     extern __shared__ __align__(16) unsigned char smem[];
-    uint32_t *Bs = reinterpret_cast<uint32_t *>(smem);                 // [NBUF][BN][LSB]
-    int *Ts = reinterpret_cast<int *>(Bs + NBUF * BN * LSB);           // [BN] thresholds
-    uint32_t *Ps = reinterpret_cast<uint32_t *>(Ts + BN);              // [ni][ph][pw][CWP]
+    uint32_t *Bs = reinterpret_cast<uint32_t *>(smem);                 // [NBUF][BN][LSB] weights
+    float *Ts = reinterpret_cast<float *>(Bs + NBUF * BN * LSB);       // [BN] accumulator start values
+    uint32_t *Os = reinterpret_cast<uint32_t *>(Ts + BN);              // [64*TM][BW] output tile
+    uint32_t *Ps = Os + 64 * TM * BW;                                  // [1 or 2][patch_words]
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -111,89 +156,25 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     const int l32 = lane & 31, half = lane >> 5;
 
     // XCD-aware order: hardware deals consecutive block ids round-robin to the 8 XCDs (one L2
-    // each); renumber so that blocks sharing an input patch (the channel tiles of one pixel
-    // tile) run on the same XCD and the patch is fetched from HBM once.
+    // each); renumber so that blocks working on the same pixel tile (its channel tiles) share
+    // an XCD and the patch is fetched from HBM once.
     int bid = blockIdx.x;
     if ((gridDim.x & 7) == 0) bid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int co_tile = bid % g.n_co_tiles; bid /= g.n_co_tiles;
-    const int tile_x = bid % g.tiles_x;     bid /= g.tiles_x;
-    const int tile_y = bid % g.tiles_y;     bid /= g.tiles_y;
-    const int img0 = bid * g.ni;
+    const int co_tile = bid % g.n_co_tiles;
+    const int slot = bid / g.n_co_tiles;
     const int th = 1 << g.lth, tw = 1 << g.ltw;
-    const int y0 = tile_y * th, x0 = tile_x * tw;
     const int o_blk = co_tile * BN;
     const int pw = tw + 2, ph = th + 2;
+    const int tiles_per_group = g.tiles_x * g.tiles_y;
 
-    // per-channel step parameters: fetched first so their latency hides behind the main loop
+    // ---- per-channel step parameters and (if resident) all weight chunks: once per block
+    const int corr = 9 * CWP * 32 - g.k_bits;          // padded positions all counted as +1
     StepWords<TN> sw;
-    if (ep.packed) {
-        sw = load_step_words<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
-        stage_thresholds(ep, o_blk, BN, g.c_out, Ts, t);
-    }
+    if (ep.packed) sw = load_step_words<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
+    stage_bias_f32(ep, o_blk, BN, g.c_out, g.k_bits + 1, corr, Ts, t);
+    const float *Tw = Ts + wn * TN * 32;               // this wave's channels
 
-    // ---- stage the input patch (halo included; outside the image / beyond cw = zero words).
-    // Four units per thread are loaded before any is stored, so the loads overlap.
-    {
-        constexpr int UPP = CWP / V;                  // units per pixel
-        const int total = g.ni * ph * pw * UPP;
-        const bool vec_ok = (g.cw % V) == 0;
-        for (int base = 0; base < total; base += 256 * 4) {
-            vec_t v[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int idx = base + k * 256 + t;
-#pragma unroll
-                for (int q = 0; q < V; ++q) vec_set(v[k], q, 0u);
-                if (idx < total) {
-                    const int u = idx % UPP;
-                    int p = idx / UPP;
-                    const int px = p % pw; p /= pw;
-                    const int py = p % ph;
-                    const int il = p / ph;
-                    const int y = y0 + py - 1, x = x0 + px - 1, img = img0 + il;
-                    if (img < g.n && y >= 0 && y < g.h && x >= 0 && x < g.w) {
-                        const uint32_t *src = in + (((int64_t)img * g.h + y) * g.w + x) * g.cw + u * V;
-                        if (vec_ok) {
-                            if (u * V < g.cw) v[k] = *reinterpret_cast<const vec_t *>(src);
-                        } else {
-#pragma unroll
-                            for (int q = 0; q < V; ++q)
-                                if (u * V + q < g.cw) vec_set(v[k], q, src[q]);
-                        }
-                    }
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int idx = base + k * 256 + t;
-                if (idx < total) *reinterpret_cast<vec_t *>(Ps + idx * V) = v[k];
-            }
-        }
-    }
-
-    // ---- this lane's pixels: implicit-GEMM row p = 4 * window + (2*dy + dx)
-    int pixoff[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int p = wm * TM * 32 + i * 32 + l32;
-        const int wq = p >> 2, sub = p & 3;
-        const int wx = wq & ((tw >> 1) - 1);
-        const int wy = (wq >> (g.ltw - 1)) & ((th >> 1) - 1);
-        const int il = wq >> (g.ltw - 1 + g.lth - 1);
-        const int py = 2 * wy + (sub >> 1), px = 2 * wx + (sub & 1);
-        pixoff[i] = ((il * ph + py) * pw + px) * CWP + half * WPH;
-    }
-    const int browoff = (wn * TN * 32 + l32) * LSB + half * SPC;
-
-    v16f acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // ---- weight staging: LDS row = [half 0: SPC words][half 1: SPC words]; the word of
+    // weight staging: LDS row = [half 0: SPC words][half 1: SPC words]; the word of
     // (half, step) is W[o][tap][half*WPH + cwi] with tap = step / WPH, cwi = step % WPH.
     vec_t pb[STG];
     const bool wvec_ok = (g.cw % V) == 0;
@@ -223,156 +204,233 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
             pb[r] = v;
         }
     };
+    auto store_w = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < STG; ++r) {
+            const int idx = t + 256 * r;
+            const int row = idx / UPRW, u = idx % UPRW;
+            if (row < BN) *reinterpret_cast<vec_t *>(Bs + (buf * BN + row) * LSB + u * V) = pb[r];
+        }
+    };
     if (RES) {
-        // every chunk: loads of all chunks are in flight together, then one barrier
-        vec_t all[NCHUNK][STG];
 #pragma unroll
         for (int c = 0; c < NCHUNK; ++c) {
             load_w(c);
-#pragma unroll
-            for (int r = 0; r < STG; ++r) all[c][r] = pb[r];
+            store_w(c);
         }
-#pragma unroll
-        for (int c = 0; c < NCHUNK; ++c)
-#pragma unroll
-            for (int r = 0; r < STG; ++r) {
-                const int idx = t + 256 * r;
-                const int row = idx / UPRW, u = idx % UPRW;
-                if (row < BN) *reinterpret_cast<vec_t *>(Bs + (c * BN + row) * LSB + u * V) = all[c][r];
-            }
-        __syncthreads();
-    } else {
-        load_w(0);
     }
+
+    // ---- patch fetch, global -> LDS directly.  Unit = 16 bytes (a whole-pixel multiple) when
+    // the layer has exactly CWP words per pixel and CWP >= 4, else one word.
+    const bool wide = (g.cw == CWP) && (CWP >= 4);
+    auto fetch_patch = [&](int ptile, int buf) {
+        const int group = ptile / tiles_per_group, rem = ptile - group * tiles_per_group;
+        const int tile_y = rem / g.tiles_x, tile_x = rem - tile_y * g.tiles_x;
+        const int img0 = group * g.ni;
+        const int y0 = tile_y * th, x0 = tile_x * tw;
+        const int imgs = min(g.ni, g.n - img0);
+        const uint32_t *base = in + (int64_t)img0 * g.h * g.w * g.cw;
+        const unsigned bytes = (unsigned)imgs * g.h * g.w * g.cw * 4;
+        const v4i rsrc = make_raw_rsrc(base, bytes);
+        // LDS byte address of the destination buffer
+        const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) uint32_t *)(Ps + buf * g.patch_words);
+        const int upp = wide ? CWP / 4 : CWP;               // units per pixel
+        const int total = g.ni * ph * pw * upp;
+        for (int b0 = 0; b0 < total; b0 += 256) {
+            const int idx = b0 + t;
+            // idx -> (image, row, column, unit) of the patch; divisions by multiply-high
+            const int p0 = idx / upp, u = idx - p0 * upp;
+            const int p1 = (int)__umulhi((unsigned)p0, g.mg_pw), px = p0 - p1 * pw;
+            const int il = (int)__umulhi((unsigned)p1, g.mg_ph), py = p1 - il * ph;
+            const int y = y0 + py - 1, x = x0 + px - 1;
+            const bool inside = y >= 0 && y < g.h && x >= 0 && x < g.w && (wide || u < g.cw);
+            unsigned voff = 0x80000000u;                    // past the end of the buffer: zeros
+            if (inside) voff = (unsigned)(((il * g.h + y) * g.w + x) * g.cw) * 4u + (unsigned)u * (wide ? 16u : 4u);
+            const unsigned wave_base = (unsigned)__builtin_amdgcn_readfirstlane(b0 + wave * 64);
+            if (idx < total) {
+                if (wide) lds_dma16(rsrc, dst + wave_base * 16u, voff);
+                else lds_dma4(rsrc, dst + wave_base * 4u, voff);
+            }
+        }
+    };
+
+    // ---- this lane's pixels: implicit-GEMM row p = 4 * window + (2*dy + dx)
+    int pixoff[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int p = wm * TM * 32 + i * 32 + l32;
+        const int wq = p >> 2, sub = p & 3;
+        const int wx = wq & ((tw >> 1) - 1);
+        const int wy = (wq >> (g.ltw - 1)) & ((th >> 1) - 1);
+        const int il = wq >> (g.ltw - 1 + g.lth - 1);
+        const int py = 2 * wy + (sub >> 1), px = 2 * wx + (sub & 1);
+        pixoff[i] = ((il * ph + py) * pw + px) * CWP + half * WPH;
+    }
+    const int browoff = (wn * TN * 32 + l32) * LSB + half * SPC;
 
     uint32_t sgn = 0x88888888u, one = 0x22222222u;
     asm volatile("" : "+s"(sgn));
     asm volatile("" : "+v"(one));
     constexpr int VPM = (7 * (TM + TN) + TM * TN - 1) / (TM * TN);
 
-    for (int c = 0; c < NCHUNK; ++c) {
-        if (!RES) {
-            __syncthreads();      // patch staged (first pass) / previous chunk consumed
-#pragma unroll
-            for (int r = 0; r < STG; ++r) {
-                const int idx = t + 256 * r;
-                const int row = idx / UPRW, u = idx % UPRW;
-                if (row < BN) *reinterpret_cast<vec_t *>(Bs + row * LSB + u * V) = pb[r];
-            }
-            __syncthreads();
-            if (c + 1 < NCHUNK) load_w(c + 1);
-        }
-        const uint32_t *Bc = RES ? Bs + c * BN * LSB : Bs;
+    if (slot < g.n_ptiles) fetch_patch(slot, 0);
 
-        // raw words of V-step group vg: TM pixels' words and TN channels' words
-        vec_t ra[2][TM], rb[2][TN];
-        auto load_group = [&](int vg, int slot) {
-            const int s = c * SPC + vg * V;
-            const int tap = s / WPH, cwi = s % WPH;
-            const int ti = tap / 3, tj = tap - ti * 3;
-            const int aoff = (ti * pw + tj) * CWP + cwi;
+    int it = 0;
+    for (int ptile = slot; ptile < g.n_ptiles; ptile += g.slots, ++it) {
+        const int buf = g.dbuf ? (it & 1) : 0;
+        const uint32_t *Pc = Ps + buf * g.patch_words;
+        if (!RES) load_w(0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this tile's patch has landed
+        __syncthreads();                                      // ... for every wave; previous tile fully consumed
+        if (g.dbuf && ptile + g.slots < g.n_ptiles) fetch_patch(ptile + g.slots, buf ^ 1);
+
+        // accumulators start at the channels' biases (see stage_bias_f32)
+        v16f acc[TM][TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) ra[slot][i] = *reinterpret_cast<const vec_t *>(Ps + pixoff[i] + aoff);
+        for (int j = 0; j < TN; ++j) {
+            const v16f b16 = load_bias16<v16f>(Tw + j * 32, half);
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                rb[slot][j] = *reinterpret_cast<const vec_t *>(Bc + browoff + j * 32 * LSB + vg * V);
-        };
-        load_group(0, 0);
-        v8i a[2][TM], b[2][TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a[0][i] = expand_fp4(vec_word(ra[0][i], 0), sgn, one);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[0][j] = expand_fp4(vec_word(rb[0][j], 0), sgn, one);
-#pragma unroll
-        for (int st = 0; st < SPC; ++st) {
-            const int cur = st & 1, nxt = cur ^ 1;
-            const int vg = st / V, q = st % V;
-            if (q == 0 && vg + 1 < NVG) load_group(vg + 1, (vg + 1) & 1);
-            if (st + 1 < SPC) {
-                const int vg1 = (st + 1) / V, q1 = (st + 1) % V;
-#pragma unroll
-                for (int i = 0; i < TM; ++i) a[nxt][i] = expand_fp4(vec_word(ra[vg1 & 1][i], q1), sgn, one);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) b[nxt][j] = expand_fp4(vec_word(rb[vg1 & 1][j], q1), sgn, one);
+            for (int i = 0; i < TM; ++i) acc[i][j] = b16;
+        }
+
+        for (int c = 0; c < NCHUNK; ++c) {
+            if (!RES) {
+                if (c > 0) __syncthreads();       // previous chunk consumed
+                store_w(0);
+                __syncthreads();
+                if (c + 1 < NCHUNK) load_w(c + 1);
             }
+            const uint32_t *Bc = RES ? Bs + c * BN * LSB : Bs;
+
+            // raw words of V-step group vg: TM pixels' words and TN channels' words
+            vec_t ra[2][TM], rb[2][TN];
+            auto load_group = [&](int vg, int slot2) {
+                const int s = c * SPC + vg * V;
+                const int tap = s / WPH, cwi = s % WPH;
+                const int ti = tap / 3, tj = tap - ti * 3;
+                const int aoff = (ti * pw + tj) * CWP + cwi;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i) ra[slot2][i] = *reinterpret_cast<const vec_t *>(Pc + pixoff[i] + aoff);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    // weights first: accumulator rows = channels, columns (lanes) = pixels
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        b[cur][j], a[cur][i], acc[i][j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                    rb[slot2][j] = *reinterpret_cast<const vec_t *>(Bc + browoff + j * 32 * LSB + vg * V);
+            };
+            load_group(0, 0);
+            v8i a[2][TM], b[2][TN];
 #pragma unroll
-            for (int k = 0; k < TM * TN; ++k) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
+            for (int i = 0; i < TM; ++i) a[0][i] = expand_fp4(vec_word(ra[0][i], 0), sgn, one);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[0][j] = expand_fp4(vec_word(rb[0][j], 0), sgn, one);
+#pragma unroll
+            for (int st = 0; st < SPC; ++st) {
+                const int cur = st & 1, nxt = cur ^ 1;
+                const int vg = st / V, q = st % V;
+                if (q == 0 && vg + 1 < NVG) load_group(vg + 1, (vg + 1) & 1);
+                if (st + 1 < SPC) {
+                    const int vg1 = (st + 1) / V, q1 = (st + 1) % V;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) a[nxt][i] = expand_fp4(vec_word(ra[vg1 & 1][i], q1), sgn, one);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) b[nxt][j] = expand_fp4(vec_word(rb[vg1 & 1][j], q1), sgn, one);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        // weights first: accumulator rows = channels, columns (lanes) = pixels
+                        // zero scale operands select the instruction form without block scales
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            b[cur][j], a[cur][i], acc[i][j], 4, 4, 0, 0, 0, 0);
+#pragma unroll
+                for (int k = 0; k < TM * TN; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
+                }
             }
         }
-    }
 
-    // ---- epilogue (shared with the first layer): sums minus the padded positions, which all
-    // counted as +1
-    const int corr = 9 * CWP * 32 - g.k_bits;
-    TilePos pos;
-    pos.n = g.n; pos.h = g.h; pos.w = g.w; pos.c_out = g.c_out;
-    pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = img0; pos.y0 = y0; pos.x0 = x0;
-    auto getx = [&](int i, int j, int r) { return (int)acc[i][j][r] - corr; };
-    if (ep.preact) conv_tile_store_preact<TM, TN>(getx, wm * TM * 32, o_blk + wn * TN * 32, l32, half, pos, ep.preact);
-    if (ep.packed) {
-        // bits -> LDS tile [output pixel][2*TN words] (reusing the weight buffer) -> coalesced stores
-        constexpr int BW = 2 * TN;
-        __syncthreads();                      // every wave is done with the weight chunk
-        conv_tile_step_to_lds<TM, TN>(getx, wm * TM * 32, wn * TN, BW, l32, half, Ts + wn * TN * 32, sw, ep.pool,
-                                      ep.pool_first != 0, Bs);
-        __syncthreads();
-        conv_tile_copy_out<BW>(Bs, 64 * TM, o_blk >> 5, pos, ep, t);
+        // ---- epilogue (shared with the first layer)
+        const int group = ptile / tiles_per_group, rem = ptile - group * tiles_per_group;
+        const int tile_y = rem / g.tiles_x, tile_x = rem - tile_y * g.tiles_x;
+        TilePos pos;
+        pos.n = g.n; pos.h = g.h; pos.w = g.w; pos.c_out = g.c_out;
+        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = group * g.ni; pos.y0 = tile_y * th; pos.x0 = tile_x * tw;
+        if (ep.preact) {
+            auto getx = [&](int i, int j, int r) {
+                return (int)(acc[i][j][r] - Tw[j * 32 + (r >> 2) * 8 + half * 4 + (r & 3)]) - corr;
+            };
+            conv_tile_store_preact<TM, TN>(getx, wm * TM * 32, o_blk + wn * TN * 32, l32, half, pos, ep.preact);
+        }
+        if (ep.packed) {
+            // bits -> LDS tile [output pixel][2*TN words] -> one vector store per pixel
+            auto gets = [&](int i, int j, int r) { return acc[i][j][r]; };
+            conv_tile_step_to_lds<TM, TN>(gets, wm * TM * 32, wn * TN, BW, l32, half, sw,
+                                          ep.pool, ep.pool_first != 0, Os);
+            __syncthreads();
+            conv_tile_copy_out<BW>(Os, 64 * TM, o_blk >> 5, pos, ep, t);
+        }
+        if (!g.dbuf && ptile + g.slots < g.n_ptiles) {
+            __syncthreads();                                  // every wave is done with the only patch buffer
+            fetch_patch(ptile + g.slots, 0);
+        }
     }
-}
-
-ConvGeom make_geom(int n, int h, int w, int c_in, int c_out, int pixels, int bn)
-{
-    ConvGeom g;
-    g.n = n; g.h = h; g.w = w;
-    g.cw = (c_in + 31) / 32;
-    g.c_out = c_out;
-    g.k_bits = 9 * c_in;
-    const TileShape ts = make_tile_shape(h, w, pixels);
-    g.ltw = ts.ltw; g.lth = ts.lth; g.ni = ts.ni;
-    g.tiles_x = ts.tiles_x; g.tiles_y = ts.tiles_y;
-    g.n_co_tiles = (c_out + bn - 1) / bn;
-    return g;
 }
 
 template <int TM, int TN, int WPH>
-size_t smem_bytes(const ConvGeom &g)
+bool make_geom(int n, int h, int w, int c_in, int c_out, ConvGeom &g, size_t &smem)
 {
     constexpr int V = WPH >= 4 ? 4 : WPH;
     constexpr int LSB = 2 * steps_per_chunk(WPH) + V;
     constexpr int NBUF = weights_resident(TM, TN, WPH) ? 9 * WPH / steps_per_chunk(WPH) : 1;
-    const size_t patch = (size_t)g.ni * ((1 << g.lth) + 2) * ((1 << g.ltw) + 2) * (2 * WPH) * 4;
-    return (size_t)NBUF * 64 * TN * LSB * 4 + 64 * TN * 4 + patch;
+    g.n = n; g.h = h; g.w = w;
+    g.cw = (c_in + 31) / 32;
+    g.c_out = c_out;
+    g.k_bits = 9 * c_in;
+    const TileShape ts = make_tile_shape(h, w, 64 * TM);
+    g.ltw = ts.ltw; g.lth = ts.lth; g.ni = ts.ni;
+    g.tiles_x = ts.tiles_x; g.tiles_y = ts.tiles_y;
+    g.n_co_tiles = (c_out + 64 * TN - 1) / (64 * TN);
+    const int64_t ptiles = (int64_t)ts.tiles_x * ts.tiles_y * ((n + ts.ni - 1) / ts.ni);
+    if (ptiles > 0x3fffffffLL || (int64_t)ts.ni * h * w * g.cw * 4 >= 0x7fffffffLL) return false;
+    g.n_ptiles = (int)ptiles;
+    // exact for dividends below 2^16 (a patch has at most a few thousand units)
+    g.mg_pw = (unsigned)((0x100000000ULL + (1 << ts.ltw) + 1) / ((1 << ts.ltw) + 2));
+    g.mg_ph = (unsigned)((0x100000000ULL + (1 << ts.lth) + 1) / ((1 << ts.lth) + 2));
+    // one patch buffer: pixels x padded words, rounded up to a wave's worth of 16-byte units
+    const int pwords = ts.ni * ((1 << ts.lth) + 2) * ((1 << ts.ltw) + 2) * (2 * WPH);
+    g.patch_words = (pwords + 255) & ~255;
+    const size_t fixed = (size_t)NBUF * 64 * TN * LSB * 4 + 64 * TN * 4 + (size_t)64 * TM * 2 * TN * 4;
+    g.dbuf = (fixed + 2 * (size_t)g.patch_words * 4 <= (size_t)MAX_SMEM) ? 1 : 0;
+    smem = fixed + (size_t)(g.dbuf ? 2 : 1) * g.patch_words * 4;
+    // persistent grid: two resident blocks per compute unit, a whole number of channel-tile sets
+    int slots = 512 / g.n_co_tiles;
+    if (slots < 1) slots = 1;
+    if (slots > g.n_ptiles) slots = g.n_ptiles;
+    g.slots = slots;
+    return smem <= (size_t)MAX_SMEM;
 }
 
 template <int TM, int TN, int WPH>
 bnn_status launch_one(const uint32_t *in, const uint32_t *wt, int n, int h, int w, int c_in, int c_out,
                       const EpiArgs &ep, hipStream_t s)
 {
-    ConvGeom g = make_geom(n, h, w, c_in, c_out, 64 * TM, 64 * TN);
-    const size_t smem = smem_bytes<TM, TN, WPH>(g);
-    const int64_t blocks = (int64_t)g.n_co_tiles * g.tiles_x * g.tiles_y * ((n + g.ni - 1) / g.ni);
-    if (smem > (size_t)MAX_SMEM || blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((bconv_mfma<TM, TN, WPH>), dim3((unsigned)blocks), dim3(256), smem, s, in, wt, g, ep);
+    ConvGeom g;
+    size_t smem;
+    if (!make_geom<TM, TN, WPH>(n, h, w, c_in, c_out, g, smem)) return BNN_ERR_UNSUPPORTED;
+    const unsigned blocks = (unsigned)(g.slots * g.n_co_tiles);
+    hipLaunchKernelGGL((bconv_mfma<TM, TN, WPH>), dim3(blocks), dim3(256), smem, s, in, wt, g, ep);
     return hip_result(hipGetLastError());
 }
 
-// Blocks a (64*TM pixels) x (64*TN channels) block tile would give, or -1 if its LDS
-// footprint does not fit.
+// Work items (pixel tiles x channel tiles) a (64*TM pixels) x (64*TN channels) block tile
+// would give, or -1 if its LDS footprint does not fit.
 template <int TM, int TN, int WPH>
 int64_t blocks_one(int n, int h, int w, int c_in, int c_out)
 {
-    ConvGeom g = make_geom(n, h, w, c_in, c_out, 64 * TM, 64 * TN);
-    if (smem_bytes<TM, TN, WPH>(g) > (size_t)MAX_SMEM) return -1;
-    return (int64_t)g.n_co_tiles * g.tiles_x * g.tiles_y * ((n + g.ni - 1) / g.ni);
+    ConvGeom g;
+    size_t smem;
+    if (!make_geom<TM, TN, WPH>(n, h, w, c_in, c_out, g, smem)) return -1;
+    return (int64_t)g.n_co_tiles * g.n_ptiles;
 }
 
 // Largest block tile that fits LDS and still fills most of the 256 compute units.

@@ -5,7 +5,7 @@
 //
 // Dense tiles run on the matrix cores: each 32-bit word of packed operand bits is expanded
 // in registers into 32 FP4 (E2M1) values +-1.0 and fed to
-// v_mfma_scale_f32_32x32x64_f8f6f4 (scales = 1.0).  Products are +-1 and partial sums are
+// v_mfma_f32_32x32x64_f8f6f4 (the form without block scales).  Products are +-1 and partial sums are
 // integers below 2^24, so the FP32 accumulators are exact.  Both operands use the same
 // bit -> sign map (bit 1 -> -1.0) and the same permutation of K inside a word, neither of
 // which changes a dot product.  Zero-filled words beyond K (and the zero tail bits of the
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        a[cur][i], b[cur][j], acc[i][j], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                        a[cur][i], b[cur][j], acc[i][j], 4, 4, 0, 0, 0, 0);
             // interleave: one MFMA, then its share of the next step's VALU work
 #pragma unroll
             for (int k = 0; k < TM * TN; ++k) {

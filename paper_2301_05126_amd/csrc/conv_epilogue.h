@@ -4,16 +4,19 @@
 // weight operand is the MFMA's first matrix, so accumulator register r of lane (l32, half)
 // is output channel 8*(r/4) + 4*half + r%4 of the tile and pixel l32.  A lane therefore
 // owns 16 channels of one pixel:
-//   - the step layer (paper Sec. II-A) is, per register, a subtract and a funnel shift that
-//     appends the sign bit of (thr - x) to a 16-bit code (x > thr  <=>  thr - x < 0);
+//   - the step layer (paper Sec. II-A) costs one instruction per value: the accumulators do
+//     not start at zero but at a per-channel bias chosen so that the finished sum
+//     s = x - thr - 1 (integer sums) or x - thr - 1/2 (FP32 sums) is negative exactly when
+//     x <= thr, and a funnel shift appends the sign bit of s to a 16-bit code;
 //   - the four nibbles of the code are spread to their channel positions, the two lane
-//     halves are merged, the per-channel flip word is xor-ed in: one packed word per pixel;
+//     halves are merged, and the word is xor-ed with the complement of the per-channel flip
+//     word (sign bit set means step = 0): one packed word per pixel;
 //   - pixels are numbered window-major inside the block (GEMM row = 4 * window + 2*dy + dx,
 //     windows x-fastest over the spatial tile, then over the block's images), so a 2x2 pool
 //     window is four neighbouring lanes: max-pool after the step is an OR over a lane quad,
 //     max-pool before the step a max over the quad (DPP quad permutes).
-// Thresholds sit in LDS (clamped to +-2^30, which no sum can reach, so thr - x never
-// overflows); words go to an LDS output tile and leave as one vector store per pixel.
+// The biases sit in LDS (thresholds clamped to a range no sum can leave, so that nothing
+// overflows or rounds); words go to an LDS output tile and leave as one vector store per pixel.
 #ifndef BNN_CONV_EPILOGUE_H
 #define BNN_CONV_EPILOGUE_H
 
@@ -72,23 +75,62 @@ __device__ __forceinline__ void conv_tile_store_preact(GetX getx, int row0, int 
     }
 }
 
-// Block-cooperative: thresholds of the block's `nch` channels (first one ch_blk0) into LDS,
-// clamped to +-2^30; channels beyond c_out get 0.  Followed by a barrier before use.
-__device__ __forceinline__ void stage_thresholds(const EpiArgs &ep, int ch_blk0, int nch, int c_out,
-                                                 int *thr_lds, int t)
+// Block-cooperative: accumulator start values of the block's `nch` channels (first one
+// ch_blk0) into LDS; followed by a barrier before use.  With a step layer the start value of
+// channel c is -(thr_c clamped to +-bound) - 1, otherwise 0: a sum x then ends as
+// x - thr - 1, negative iff x <= thr.  |x| <= bound - 1 must hold for every reachable sum.
+__device__ __forceinline__ void stage_bias_i32(const EpiArgs &ep, int ch_blk0, int nch, int c_out, int bound,
+                                               int *bias_lds, int t)
 {
     for (int c = t; c < nch; c += 256) {
         int v = 0;
-        if (ch_blk0 + c < c_out) v = ep.thr[ch_blk0 + c];
-        v = v > (1 << 30) ? (1 << 30) : (v < -(1 << 30) ? -(1 << 30) : v);
-        thr_lds[c] = v;
+        if (ep.packed && ch_blk0 + c < c_out) {
+            v = ep.thr[ch_blk0 + c];
+            v = v > bound ? bound : (v < -bound ? -bound : v);
+            v = -v - 1;
+        }
+        bias_lds[c] = v;
     }
 }
 
-// Per 32-channel tile of a wave: packed words of the flipped / existing channels.
+// FP32 accumulators whose raw sum is x + corr (corr >= 0: padded positions all count +1):
+// start value -(thr_c clamped) - corr - 1/2 with a step layer, otherwise -corr, so the sum
+// ends as x - thr - 1/2 (never zero, negative iff x <= thr) or as x.  All values are
+// multiples of 1/2 far below 2^23: exact.
+__device__ __forceinline__ void stage_bias_f32(const EpiArgs &ep, int ch_blk0, int nch, int c_out, int bound,
+                                               int corr, float *bias_lds, int t)
+{
+    for (int c = t; c < nch; c += 256) {
+        float v = -(float)corr;
+        if (ep.packed) {
+            int th = 0;
+            if (ch_blk0 + c < c_out) th = ep.thr[ch_blk0 + c];
+            th = th > bound ? bound : (th < -bound ? -bound : th);
+            v = -(float)(th + corr) - 0.5f;
+        }
+        bias_lds[c] = v;
+    }
+}
+
+// This lane's 16 start values of a 32-channel tile (channels 8q + 4*half + (0..3), q = 0..3),
+// in accumulator register order.  bias_tile = LDS start values of the tile's first channel.
+template <typename VecT, typename T>
+__device__ __forceinline__ VecT load_bias16(const T *bias_tile, int half)
+{
+    VecT v;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        struct alignas(16) Quad { T a, b, c, d; };
+        const Quad f = *reinterpret_cast<const Quad *>(bias_tile + q * 8 + half * 4);
+        v[q * 4] = f.a; v[q * 4 + 1] = f.b; v[q * 4 + 2] = f.c; v[q * 4 + 3] = f.d;
+    }
+    return v;
+}
+
+// Per 32-channel tile of a wave: packed words of the not-flipped / existing channels.
 template <int TN>
 struct StepWords {
-    unsigned flipw[TN], okw[TN];
+    unsigned nflipw[TN], okw[TN];
 };
 
 template <int TN>
@@ -99,7 +141,7 @@ __device__ __forceinline__ StepWords<TN> load_step_words(const EpiArgs &ep, int 
     for (int j = 0; j < TN; ++j) {
         const int col = ch0 + j * 32 + l32;
         const bool cok = col < c_out;
-        sw.flipw[j] = (unsigned)__ballot(cok && ep.flip && ep.flip[col]);      // lanes 0..31 = channels
+        sw.nflipw[j] = ~(unsigned)__ballot(cok && ep.flip && ep.flip[col]);    // lanes 0..31 = channels
         sw.okw[j] = (unsigned)__ballot(cok);
     }
     return sw;
@@ -109,41 +151,48 @@ __device__ __forceinline__ StepWords<TN> load_step_words(const EpiArgs &ep, int 
 __device__ __forceinline__ int quad_xor1(int v) { return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false); }
 __device__ __forceinline__ int quad_xor2(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false); }
 
+// maximum over the four lanes of a quad
+__device__ __forceinline__ int quad_max(int v)
+{
+    v = max(v, quad_xor1(v));
+    return max(v, quad_xor2(v));
+}
+__device__ __forceinline__ float quad_max(float v)
+{
+    v = fmaxf(v, __int_as_float(quad_xor1(__float_as_int(v))));
+    return fmaxf(v, __int_as_float(quad_xor2(__float_as_int(v))));
+}
+__device__ __forceinline__ unsigned value_bits(int v) { return (unsigned)v; }
+__device__ __forceinline__ unsigned value_bits(float v) { return __float_as_uint(v); }
+
 // Step (+ pool) of one wave's tiles into the block's LDS output tile.
-// out_lds is [output pixel of the block][bw words]; an output pixel is a GEMM row (pool 1) or
-// a window (pool 2).  word0 = index, inside the block's bw words, of this wave's first 32
-// channels; thr_wave = LDS thresholds of this wave's first channel.
-template <int TM, int TN, typename GetX>
-__device__ __forceinline__ void conv_tile_step_to_lds(GetX getx, int row0, int word0, int bw, int l32, int half,
-                                                      const int *thr_wave, const StepWords<TN> &sw, int pool,
-                                                      bool pool_first, uint32_t *out_lds)
+// gets(i, j, r): finished biased sum (int or float) of pixel tile i, channel tile j, register
+// r; its sign bit is set iff x <= thr.  out_lds is [output pixel of the block][bw words]; an
+// output pixel is a GEMM row (pool 1) or a window (pool 2).  word0 = index, inside the
+// block's bw words, of this wave's first 32 channels.
+template <int TM, int TN, typename GetS>
+__device__ __forceinline__ void conv_tile_step_to_lds(GetS gets, int row0, int word0, int bw, int l32, int half,
+                                                      const StepWords<TN> &sw, int pool, bool pool_first,
+                                                      uint32_t *out_lds)
 {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        // this lane's 16 thresholds: channels 8q + 4*half + (0..3), q = 0..3
-        int thr[16];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int4 t4 = *reinterpret_cast<const int4 *>(thr_wave + j * 32 + q * 8 + half * 4);
-            thr[q * 4] = t4.x; thr[q * 4 + 1] = t4.y; thr[q * 4 + 2] = t4.z; thr[q * 4 + 3] = t4.w;
-        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            unsigned code = 0;                       // bit r = (x_r > thr_r)
+            unsigned code = 0;                       // bit r = (x_r <= thr_r)
+            if (pool == 2 && pool_first) {           // max over the window's four pixels first
 #pragma unroll
-            for (int r = 15; r >= 0; --r) {
-                int x = getx(i, j, r);
-                if (pool == 2 && pool_first) {       // max over the window's four pixels first
-                    x = max(x, quad_xor1(x));
-                    x = max(x, quad_xor2(x));
-                }
-                code = __builtin_amdgcn_alignbit(code, (unsigned)(thr[r] - x), 31);
+                for (int r = 15; r >= 0; --r)
+                    code = __builtin_amdgcn_alignbit(code, value_bits(quad_max(gets(i, j, r))), 31);
+            } else {
+#pragma unroll
+                for (int r = 15; r >= 0; --r) code = __builtin_amdgcn_alignbit(code, value_bits(gets(i, j, r)), 31);
             }
             // nibble q of the code -> channels 8q + 4*half .. +3
             unsigned w = (code & 0xFu) | ((code & 0xF0u) << 4) | ((code & 0xF00u) << 8) | ((code & 0xF000u) << 12);
             w <<= 4 * half;
             w |= (unsigned)__shfl_xor((int)w, 32);
-            w = (w ^ sw.flipw[j]) & sw.okw[j];
+            w = (w ^ sw.nflipw[j]) & sw.okw[j];
             const int row = row0 + i * 32 + l32;
             if (pool == 2) {
                 if (!pool_first) {                   // OR over the window

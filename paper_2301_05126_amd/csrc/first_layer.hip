@@ -237,13 +237,13 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
     const unsigned *P32 = reinterpret_cast<const unsigned *>(Pl);
 
     // per-channel step parameters, fetched once per block (the first barrier of the tile
-    // loop publishes the thresholds)
+    // loop publishes the accumulator start values; sums stay far below 2^30)
     StepWords<TN> sw[NG];
     if (ep.packed) {
 #pragma unroll
         for (int grp = 0; grp < NG; ++grp) sw[grp] = load_step_words<TN>(ep, o_blk + grp * 64, l32, g.c_out);
-        stage_thresholds(ep, o_blk, 64 * NG, g.c_out, Tl, t);
     }
+    stage_bias_i32(ep, o_blk, 64 * NG, g.c_out, 1 << 30, Tl, t);
 
     // ---- persistent loop over (image group, tile) work items
     for (int item = blockIdx.x; item < g.n_items; item += gridDim.x) {
@@ -310,13 +310,15 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
 
 #pragma unroll 1
         for (int grp = 0; grp < NG; ++grp) {
+            // accumulators start at the channels' biases (see stage_bias_i32)
+            const int *Tg = Tl + grp * 64;
             v16i acc[2][TN];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < TN; ++j) {
+                const v16i b16 = load_bias16<v16i>(Tg + j * 32, half);
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+                for (int i = 0; i < 2; ++i) acc[i][j] = b16;
+            }
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 if (ks >= nsteps) break;
@@ -328,16 +330,21 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a[ks][i], acc[i][j], 0, 0, 0);   // rows = channels
                 }
             }
-            auto getx = [&](int i, int j, int r) { return acc[i][j][r]; };
             const int ch0 = o_blk + grp * 64;
-            if (ep.preact) conv_tile_store_preact<2, TN>(getx, wave * 64, ch0, l32, half, pos, ep.preact);
+            if (ep.preact) {
+                auto getx = [&](int i, int j, int r) {
+                    return acc[i][j][r] - Tg[j * 32 + (r >> 2) * 8 + half * 4 + (r & 3)];
+                };
+                conv_tile_store_preact<2, TN>(getx, wave * 64, ch0, l32, half, pos, ep.preact);
+            }
             if (ep.packed) {
                 // select this group's words without indexing the register array dynamically
                 StepWords<TN> cur = sw[0];
 #pragma unroll
                 for (int q = 1; q < NG; ++q)
                     if (grp == q) cur = sw[q];
-                conv_tile_step_to_lds<2, TN>(getx, wave * 64, grp * TN, BW, l32, half, Tl + grp * 64, cur, ep.pool,
+                auto gets = [&](int i, int j, int r) { return acc[i][j][r]; };
+                conv_tile_step_to_lds<2, TN>(gets, wave * 64, grp * TN, BW, l32, half, cur, ep.pool,
                                              ep.pool_first != 0, Ol);
             }
         }

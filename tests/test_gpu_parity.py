@@ -127,6 +127,13 @@ CONV_SHAPES = [(1, 4, 4, 32, 8, 1), (2, 8, 8, 64, 64, 2), (3, 14, 14, 64, 64, 2)
                (600, 2, 2, 64, 64, 2), (9, 16, 16, 64, 128, 2)]
 
 
+def extreme_thresholds(thr, room, k):
+    """Overwrite up to `room` trailing thresholds with values at and beyond the range of a sum."""
+    big = [np.iinfo(np.int32).max, np.iinfo(np.int32).min, k, -k, k - 1, -k - 1, k + 1, -k + 1]
+    for q, v in enumerate(big[:room]):
+        thr[len(thr) - 1 - q] = v
+
+
 def conv_weights_packed(wt):
     co, _, _, ci = wt.shape
     return pack_pm1(wt.reshape(co * 9, ci)).reshape(co, 3, 3, (ci + 31) // 32)
@@ -145,6 +152,7 @@ def test_conv_binary_raw_and_fused(n, h, w, ci, co, pool):
     k = 9 * ci
     thr = rng.integers(-(k // 8), k // 8 + 1, size=co).astype(np.int32)
     thr[: co // 2] = want[0, 0, 0, : co // 2]         # ties at one pixel
+    extreme_thresholds(thr, co - co // 2, k)
     flip = rng.integers(0, 2, size=co).astype(np.uint8)
     s = oracle.step(want, thr, flip)
     if pool == 2:
@@ -210,6 +218,7 @@ def test_conv_first_int8(n, h, w, ci, co, kh, kw, pad, padv, pool):
     k = kh * kw * ci
     thr = rng.integers(-(k // 8), k // 8 + 1, size=co).astype(np.int32)
     thr[: co // 2] = want[0, 0, 0, : co // 2]
+    extreme_thresholds(thr, co - co // 2, 128 * k)
     flip = rng.integers(0, 2, size=co).astype(np.uint8)
     s = oracle.step(want, thr, flip)
     if pool == 2:
