@@ -91,8 +91,14 @@ __device__ __forceinline__ void lds_dma4(v4i rsrc, unsigned lds_base, unsigned v
                  :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
 }
 
+// Dword `part` (0..3) of expand_fp4.
+__device__ __forceinline__ uint32_t expand_part(uint32_t w, int part, uint32_t sgn, uint32_t one)
+{
+    return part == 3 ? ((w & sgn) | one) : (((w << (3 - part)) & sgn) | one);
+}
+
 // Steps (one MFMA K-slice = one word per lane half) per weight chunk, by words per half.
-constexpr int steps_per_chunk(int wph) { return wph == 1 ? 9 : (wph == 2 ? 6 : (wph == 4 ? 12 : 8)); }
+constexpr int steps_per_chunk(int wph) { return wph == 1 ? 9 : (wph == 2 ? 18 : (wph == 4 ? 12 : 8)); }
 
 // Whether a block keeps all of its weight chunks in LDS at once: up to 24 KB for any tile
 // (C_in <= 128), up to 48 KB for the 64-channel tile.
@@ -104,6 +110,10 @@ constexpr bool weights_resident(int tm, int tn, int wph)
     const int bytes = nchunk * 64 * tn * lsb * 4;
     return bytes <= 24 * 1024 || (tm * tn == 1 && bytes <= 48 * 1024);
 }
+
+struct TileCoord {
+    int group, ty, tx;           // image group, tile row, tile column
+};
 
 struct ConvGeom {
     int n, h, w, cw;             // input: images, height, width, words per pixel
@@ -147,8 +157,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     extern __shared__ __align__(16) unsigned char smem[];
     uint32_t *Bs = reinterpret_cast<uint32_t *>(smem);                 // [NBUF][BN][LSB] weights
     float *Ts = reinterpret_cast<float *>(Bs + NBUF * BN * LSB);       // [BN] accumulator start values
-    uint32_t *Os = reinterpret_cast<uint32_t *>(Ts + BN);              // [64*TM][BW] output tile
-    uint32_t *Ps = Os + 64 * TM * BW;                                  // [1 or 2][patch_words]
+    uint32_t *Os = reinterpret_cast<uint32_t *>(Ts + BN);              // [2][64*TM][BW] output tiles
+    uint32_t *Ps = Os + 2 * 64 * TM * BW;                              // [1 or 2][patch_words]
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -179,29 +189,46 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     vec_t pb[STG];
     const bool wvec_ok = (g.cw % V) == 0;
     auto load_w = [&](int chunk) {
-#pragma unroll
-        for (int r = 0; r < STG; ++r) {
+        // Branch-free inside each loop, so that all loads of a chunk are in flight together:
+        // rows or words that do not exist read the first weight word and are zeroed afterwards.
+        auto unit = [&](int r, bool &row_ok, int &cwpos) {
             const int idx = t + 256 * r;
             const int row = idx / UPRW, u = idx % UPRW;
             const int hh = u / NVG, vg = u % NVG;
             const int s = chunk * SPC + vg * V;
             const int tap = s / WPH, cwi = s % WPH;
-            const int cwpos = hh * WPH + cwi;
+            cwpos = hh * WPH + cwi;
             const int o = o_blk + row;
-            vec_t v;
+            row_ok = row < BN && o < g.c_out;
+            return wt + ((int64_t)o * 9 + tap) * g.cw + cwpos;
+        };
+        if (wvec_ok) {
 #pragma unroll
-            for (int q = 0; q < V; ++q) vec_set(v, q, 0u);
-            if (row < BN && o < g.c_out) {
-                const uint32_t *src = wt + ((int64_t)o * 9 + tap) * g.cw + cwpos;
-                if (wvec_ok) {
-                    if (cwpos < g.cw) v = *reinterpret_cast<const vec_t *>(src);
-                } else {
+            for (int r = 0; r < STG; ++r) {
+                bool row_ok;
+                int cwpos;
+                const uint32_t *src = unit(r, row_ok, cwpos);
+                const bool ok = row_ok && cwpos < g.cw;
+                vec_t v = *reinterpret_cast<const vec_t *>(ok ? src : wt);
 #pragma unroll
-                    for (int q = 0; q < V; ++q)
-                        if (cwpos + q < g.cw) vec_set(v, q, src[q]);
-                }
+                for (int q = 0; q < V; ++q) vec_set(v, q, ok ? vec_word(v, q) : 0u);
+                pb[r] = v;
             }
-            pb[r] = v;
+        } else {
+#pragma unroll
+            for (int r = 0; r < STG; ++r) {
+                bool row_ok;
+                int cwpos;
+                const uint32_t *src = unit(r, row_ok, cwpos);
+                vec_t v;
+#pragma unroll
+                for (int q = 0; q < V; ++q) {
+                    const bool ok = row_ok && cwpos + q < g.cw;
+                    const uint32_t x = *(ok ? src + q : wt);
+                    vec_set(v, q, ok ? x : 0u);
+                }
+                pb[r] = v;
+            }
         }
     };
     auto store_w = [&](int buf) {
@@ -223,11 +250,9 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     // ---- patch fetch, global -> LDS directly.  Unit = 16 bytes (a whole-pixel multiple) when
     // the layer has exactly CWP words per pixel and CWP >= 4, else one word.
     const bool wide = (g.cw == CWP) && (CWP >= 4);
-    auto fetch_patch = [&](int ptile, int buf) {
-        const int group = ptile / tiles_per_group, rem = ptile - group * tiles_per_group;
-        const int tile_y = rem / g.tiles_x, tile_x = rem - tile_y * g.tiles_x;
-        const int img0 = group * g.ni;
-        const int y0 = tile_y * th, x0 = tile_x * tw;
+    auto fetch_patch = [&](const TileCoord &tc, int buf) {
+        const int img0 = tc.group * g.ni;
+        const int y0 = tc.ty * th, x0 = tc.tx * tw;
         const int imgs = min(g.ni, g.n - img0);
         const uint32_t *base = in + (int64_t)img0 * g.h * g.w * g.cw;
         const unsigned bytes = (unsigned)imgs * g.h * g.w * g.cw * 4;
@@ -271,18 +296,51 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     uint32_t sgn = 0x88888888u, one = 0x22222222u;
     asm volatile("" : "+s"(sgn));
     asm volatile("" : "+v"(one));
-    constexpr int VPM = (7 * (TM + TN) + TM * TN - 1) / (TM * TN);
+    constexpr int DPM = (4 * (TM + TN) + TM * TN - 1) / (TM * TN);   // operand dwords made per MFMA
 
-    if (slot < g.n_ptiles) fetch_patch(slot, 0);
+    // tile coordinates of the previous, current and next pixel tile of this block; a step of
+    // `slots` tiles is a fixed (group, y, x) increment with carries
+    TileCoord step, prev, cur, next;
+    step.group = g.slots / tiles_per_group;
+    step.ty = (g.slots - step.group * tiles_per_group) / g.tiles_x;
+    step.tx = g.slots - step.group * tiles_per_group - step.ty * g.tiles_x;
+    next.group = slot / tiles_per_group;
+    next.ty = (slot - next.group * tiles_per_group) / g.tiles_x;
+    next.tx = slot - next.group * tiles_per_group - next.ty * g.tiles_x;
+    prev = cur = next;
+    auto advance = [&](TileCoord &c) {
+        c.tx += step.tx;
+        if (c.tx >= g.tiles_x) { c.tx -= g.tiles_x; ++c.ty; }
+        c.ty += step.ty;
+        if (c.ty >= g.tiles_y) { c.ty -= g.tiles_y; ++c.group; }
+        c.group += step.group;
+    };
+    auto tile_pos = [&](const TileCoord &c) {
+        TilePos pos;
+        pos.n = g.n; pos.h = g.h; pos.w = g.w; pos.c_out = g.c_out;
+        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = c.group * g.ni; pos.y0 = c.ty * th; pos.x0 = c.tx * tw;
+        return pos;
+    };
 
+    if (slot < g.n_ptiles) fetch_patch(next, 0);
+
+    // The packed words of a tile go to one of two LDS output tiles and are copied to global
+    // memory after the next tile's barrier, so the stores drain while the next tile is
+    // multiplied and the block needs one barrier per tile.
     int it = 0;
     for (int ptile = slot; ptile < g.n_ptiles; ptile += g.slots, ++it) {
         const int buf = g.dbuf ? (it & 1) : 0;
         const uint32_t *Pc = Ps + buf * g.patch_words;
+        uint32_t *Oc = Os + (it & 1) * (64 * TM * BW);
+        prev = cur;
+        cur = next;
+        advance(next);
         if (!RES) load_w(0);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this tile's patch has landed
         __syncthreads();                                      // ... for every wave; previous tile fully consumed
-        if (g.dbuf && ptile + g.slots < g.n_ptiles) fetch_patch(ptile + g.slots, buf ^ 1);
+        if (g.dbuf && ptile + g.slots < g.n_ptiles) fetch_patch(next, buf ^ 1);
+        if (ep.packed && it > 0)
+            conv_tile_copy_out<BW>(Os + ((it - 1) & 1) * (64 * TM * BW), 64 * TM, o_blk >> 5, tile_pos(prev), ep, t);
 
         // accumulators start at the channels' biases (see stage_bias_f32)
         v16f acc[TM][TN];
@@ -322,39 +380,50 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
 #pragma unroll
             for (int j = 0; j < TN; ++j) b[0][j] = expand_fp4(vec_word(rb[0][j], 0), sgn, one);
 #pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int q = 4; q < 8; ++q) a[1][i][q] = 0;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 4; q < 8; ++q) b[1][j][q] = 0;
+            // The instruction order below is the issue order (scheduling barriers pin it): the
+            // LDS reads of the next word group, then each MFMA followed by its share of the
+            // next step's operand dwords, so that VALU work runs in the shadow of the MFMAs.
+#pragma unroll
             for (int st = 0; st < SPC; ++st) {
                 const int cur = st & 1, nxt = cur ^ 1;
                 const int vg = st / V, q = st % V;
-                if (q == 0 && vg + 1 < NVG) load_group(vg + 1, (vg + 1) & 1);
-                if (st + 1 < SPC) {
-                    const int vg1 = (st + 1) / V, q1 = (st + 1) % V;
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) a[nxt][i] = expand_fp4(vec_word(ra[vg1 & 1][i], q1), sgn, one);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) b[nxt][j] = expand_fp4(vec_word(rb[vg1 & 1][j], q1), sgn, one);
+                if (q == 0 && vg + 1 < NVG) {
+                    load_group(vg + 1, (vg + 1) & 1);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        // weights first: accumulator rows = channels, columns (lanes) = pixels
-                        // zero scale operands select the instruction form without block scales
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            b[cur][j], a[cur][i], acc[i][j], 4, 4, 0, 0, 0, 0);
+                const int vg1 = (st + 1) / V, q1 = (st + 1) % V;
 #pragma unroll
                 for (int k = 0; k < TM * TN; ++k) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
+                    const int i = k / TN, j = k % TN;
+                    // weights first: accumulator rows = channels, columns (lanes) = pixels
+                    // (zero scale operands select the instruction form without block scales)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        b[cur][j], a[cur][i], acc[i][j], 4, 4, 0, 0, 0, 0);
+                    if (st + 1 < SPC) {
+#pragma unroll
+                        for (int d = k * DPM; d < (k + 1) * DPM && d < 4 * (TM + TN); ++d) {
+                            const int wi = d >> 2, part = d & 3;
+                            if (wi < TM)
+                                a[nxt][wi][part] = (int)expand_part(vec_word(ra[vg1 & 1][wi], q1), part, sgn, one);
+                            else
+                                b[nxt][wi - TM][part] =
+                                    (int)expand_part(vec_word(rb[vg1 & 1][wi - TM], q1), part, sgn, one);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
 
         // ---- epilogue (shared with the first layer)
-        const int group = ptile / tiles_per_group, rem = ptile - group * tiles_per_group;
-        const int tile_y = rem / g.tiles_x, tile_x = rem - tile_y * g.tiles_x;
-        TilePos pos;
-        pos.n = g.n; pos.h = g.h; pos.w = g.w; pos.c_out = g.c_out;
-        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = group * g.ni; pos.y0 = tile_y * th; pos.x0 = tile_x * tw;
+        const TilePos pos = tile_pos(cur);
         if (ep.preact) {
             auto getx = [&](int i, int j, int r) {
                 return (int)(acc[i][j][r] - Tw[j * 32 + (r >> 2) * 8 + half * 4 + (r & 3)]) - corr;
@@ -362,17 +431,19 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
             conv_tile_store_preact<TM, TN>(getx, wm * TM * 32, o_blk + wn * TN * 32, l32, half, pos, ep.preact);
         }
         if (ep.packed) {
-            // bits -> LDS tile [output pixel][2*TN words] -> one vector store per pixel
+            // bits -> LDS tile [output pixel][2*TN words]; one vector store per pixel later
             auto gets = [&](int i, int j, int r) { return acc[i][j][r]; };
             conv_tile_step_to_lds<TM, TN>(gets, wm * TM * 32, wn * TN, BW, l32, half, sw,
-                                          ep.pool, ep.pool_first != 0, Os);
-            __syncthreads();
-            conv_tile_copy_out<BW>(Os, 64 * TM, o_blk >> 5, pos, ep, t);
+                                          ep.pool, ep.pool_first != 0, Oc);
         }
         if (!g.dbuf && ptile + g.slots < g.n_ptiles) {
             __syncthreads();                                  // every wave is done with the only patch buffer
-            fetch_patch(ptile + g.slots, 0);
+            fetch_patch(next, 0);
         }
+    }
+    if (ep.packed && it > 0) {
+        __syncthreads();
+        conv_tile_copy_out<BW>(Os + ((it - 1) & 1) * (64 * TM * BW), 64 * TM, o_blk >> 5, tile_pos(cur), ep, t);
     }
 }
 
@@ -399,7 +470,7 @@ bool make_geom(int n, int h, int w, int c_in, int c_out, ConvGeom &g, size_t &sm
     // one patch buffer: pixels x padded words, rounded up to a wave's worth of 16-byte units
     const int pwords = ts.ni * ((1 << ts.lth) + 2) * ((1 << ts.ltw) + 2) * (2 * WPH);
     g.patch_words = (pwords + 255) & ~255;
-    const size_t fixed = (size_t)NBUF * 64 * TN * LSB * 4 + 64 * TN * 4 + (size_t)64 * TM * 2 * TN * 4;
+    const size_t fixed = (size_t)NBUF * 64 * TN * LSB * 4 + 64 * TN * 4 + (size_t)2 * 64 * TM * 2 * TN * 4;
     g.dbuf = (fixed + 2 * (size_t)g.patch_words * 4 <= (size_t)MAX_SMEM) ? 1 : 0;
     smem = fixed + (size_t)(g.dbuf ? 2 : 1) * g.patch_words * 4;
     // persistent grid: two resident blocks per compute unit, a whole number of channel-tile sets

@@ -8,8 +8,8 @@
 //     not start at zero but at a per-channel bias chosen so that the finished sum
 //     s = x - thr - 1 (integer sums) or x - thr - 1/2 (FP32 sums) is negative exactly when
 //     x <= thr, and a funnel shift appends the sign bit of s to a 16-bit code;
-//   - the four nibbles of the code are spread to their channel positions, the two lane
-//     halves are merged, and the word is xor-ed with the complement of the per-channel flip
+//   - the four nibbles are put at their channel positions, the two lane halves are merged
+//     (v_permlane32_swap), and the word is xor-ed with the complement of the per-channel flip
 //     word (sign bit set means step = 0): one packed word per pixel;
 //   - pixels are numbered window-major inside the block (GEMM row = 4 * window + 2*dy + dx,
 //     windows x-fastest over the spatial tile, then over the block's images), so a 2x2 pool
@@ -137,13 +137,16 @@ template <int TN>
 __device__ __forceinline__ StepWords<TN> load_step_words(const EpiArgs &ep, int ch0, int l32, int c_out)
 {
     StepWords<TN> sw;
+    uint8_t fl[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = ch0 + j * 32 + l32;
         const bool cok = col < c_out;
-        sw.nflipw[j] = ~(unsigned)__ballot(cok && ep.flip && ep.flip[col]);    // lanes 0..31 = channels
+        fl[j] = ep.flip ? ep.flip[cok ? col : 0] : (uint8_t)0;      // loads of all tiles in flight together
         sw.okw[j] = (unsigned)__ballot(cok);
     }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) sw.nflipw[j] = ~((unsigned)__ballot(fl[j] != 0) & sw.okw[j]);   // lanes 0..31 = channels
     return sw;
 }
 
@@ -179,19 +182,22 @@ __device__ __forceinline__ void conv_tile_step_to_lds(GetS gets, int row0, int w
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            unsigned code = 0;                       // bit r = (x_r <= thr_r)
+            // code[q] bit m = (x_r <= thr_r) for register r = 4q + m: channels 8q + 4*half + m
+            unsigned code[4] = {0u, 0u, 0u, 0u};
             if (pool == 2 && pool_first) {           // max over the window's four pixels first
 #pragma unroll
                 for (int r = 15; r >= 0; --r)
-                    code = __builtin_amdgcn_alignbit(code, value_bits(quad_max(gets(i, j, r))), 31);
+                    code[r >> 2] = __builtin_amdgcn_alignbit(code[r >> 2], value_bits(quad_max(gets(i, j, r))), 31);
             } else {
 #pragma unroll
-                for (int r = 15; r >= 0; --r) code = __builtin_amdgcn_alignbit(code, value_bits(gets(i, j, r)), 31);
+                for (int r = 15; r >= 0; --r)
+                    code[r >> 2] = __builtin_amdgcn_alignbit(code[r >> 2], value_bits(gets(i, j, r)), 31);
             }
-            // nibble q of the code -> channels 8q + 4*half .. +3
-            unsigned w = (code & 0xFu) | ((code & 0xF0u) << 4) | ((code & 0xF00u) << 8) | ((code & 0xF000u) << 12);
+            unsigned w = (((code[3] << 8) | code[2]) << 16) | ((code[1] << 8) | code[0]);
             w <<= 4 * half;
-            w |= (unsigned)__shfl_xor((int)w, 32);
+            // merge the two lane halves (lane l and lane l ^ 32 hold complementary nibbles)
+            const auto sw2 = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+            w = sw2[0] | sw2[1];
             w = (w ^ sw.nflipw[j]) & sw.okw[j];
             const int row = row0 + i * 32 + l32;
             if (pool == 2) {
