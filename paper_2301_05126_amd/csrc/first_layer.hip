@@ -166,8 +166,14 @@ __device__ __forceinline__ int div_magic(int n, unsigned mg) { return mg ? (int)
 // K is ordered [kernel row ti][tj*c_in + c], every kernel row zero-padded to slp bytes on
 // the weight side; the activation bytes behind a short row are whatever follows in the
 // patch and meet zero weights.
-template <int NG>
-__global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restrict__ in,
+//
+// PIPE (patch of at most 1024 bytes, i.e. four bytes per thread): the next tile's patch bytes
+// are loaded into registers before the current tile is computed and stored to the second
+// patch buffer afterwards, so their latency hides behind the tile and the block needs one
+// barrier per tile.  Otherwise the patch is staged in place between two barriers.  Packed
+// words go to one of two LDS output tiles and are copied out after the next barrier.
+template <int NG, bool PIPE>
+__global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restrict__ in,
                                                        const int8_t *__restrict__ wt, FirstGeomM g, EpiArgs ep)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -175,9 +181,9 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
     constexpr int TN = 2;                                       // 32-channel tiles per group
     constexpr int BW = 2 * NG;                                  // packed output words per pixel
     unsigned char *Wl = smem;                                   // [64*NG][ws]
-    uint32_t *Ol = reinterpret_cast<uint32_t *>(smem + 64 * NG * ws);      // [256][BW]
-    int *Tl = reinterpret_cast<int *>(smem + 64 * NG * ws + 256 * BW * 4);  // [64*NG] thresholds
-    unsigned char *Pl = smem + 64 * NG * ws + 256 * BW * 4 + 64 * NG * 4;   // [ni][ph][pw][c_in] + slack
+    uint32_t *Ol = reinterpret_cast<uint32_t *>(smem + 64 * NG * ws);          // [2][256][BW]
+    int *Tl = reinterpret_cast<int *>(smem + 64 * NG * ws + 2 * 256 * BW * 4);  // [64*NG] start values
+    unsigned char *Pl = smem + 64 * NG * ws + 2 * 256 * BW * 4 + 64 * NG * 4;   // [1 or 2] x ([ni][ph][pw][c_in] + slack)
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -234,7 +240,6 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
     }
     const int u16 = g.slp >> 4;                  // 16-byte units per kernel row
     const int nsteps = g.kp >> 5;
-    const unsigned *P32 = reinterpret_cast<const unsigned *>(Pl);
 
     // per-channel step parameters, fetched once per block (the first barrier of the tile
     // loop publishes the accumulator start values; sums stay far below 2^30)
@@ -246,112 +251,142 @@ __global__ __launch_bounds__(256, 2) void conv_first_mfma(const int8_t *__restri
     stage_bias_i32(ep, o_blk, 64 * NG, g.c_out, 1 << 30, Tl, t);
 
     // ---- persistent loop over (image group, tile) work items
-    for (int item = blockIdx.x; item < g.n_items; item += gridDim.x) {
+    struct Item { int img0, y0, x0; };
+    auto decode = [&](int item) {
+        Item c;
         int rest = item;
         const int tile_x = rest % g.tiles_x; rest /= g.tiles_x;
         const int tile_y = rest % g.tiles_y; rest /= g.tiles_y;
-        const int img0 = rest * g.ni;
-        const int y0 = tile_y * th, x0 = tile_x * tw;
-
-        __syncthreads();          // previous item's patch fully consumed (and weights staged)
-        // input patch as bytes, pad_value outside the image; the slack behind it is zeroed.
-        // Loads of four bytes per thread are issued together, then stored.
-        {
-            const int total = g.ni * ph * pw * g.c_in;
-            for (int base = 0; base < g.patch_bytes; base += 256 * 4) {
-                int v[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int idx = base + u * 256 + t;
-                    v[u] = 0;
-                    if (idx < total) {
-                        const int p0 = div_magic(idx, g.mg_cin), c = idx - p0 * g.c_in;
-                        const int p1 = div_magic(p0, g.mg_pw), px = p0 - p1 * pw;
-                        const int il = div_magic(p1, g.mg_ph), py = p1 - il * ph;
-                        const int y = y0 + py - g.pad, x = x0 + px - g.pad, img = img0 + il;
-                        v[u] = g.pad_value;
-                        if (img < g.n && y >= 0 && y < g.h && x >= 0 && x < g.w)
-                            v[u] = in[(((int64_t)img * g.h + y) * g.w + x) * g.c_in + c];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int idx = base + u * 256 + t;
-                    if (idx < g.patch_bytes) Pl[idx] = (unsigned char)(int8_t)v[u];
-                }
-            }
-        }
-        __syncthreads();
-
+        c.img0 = rest * g.ni; c.y0 = tile_y * th; c.x0 = tile_x * tw;
+        return c;
+    };
+    auto item_pos = [&](const Item &c) {
         TilePos pos;
         pos.n = g.n; pos.h = g.ho; pos.w = g.wo; pos.c_out = g.c_out;
-        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = img0; pos.y0 = y0; pos.x0 = x0;
+        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = c.img0; pos.y0 = c.y0; pos.x0 = c.x0;
+        return pos;
+    };
+    // Patch bytes base + u*256 + t (u = 0..3) of an item: pad_value outside the image, zero in
+    // the slack behind the patch.  Branch-free, so that the four loads are in flight together:
+    // bytes that are not read from the image load the tensor's first byte instead.
+    const int total = g.ni * ph * pw * g.c_in;
+    auto load_bytes = [&](const Item &c, int base, int (&v)[4]) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * 256 + t;
+            const int p0 = div_magic(idx, g.mg_cin), ch = idx - p0 * g.c_in;
+            const int p1 = div_magic(p0, g.mg_pw), px = p0 - p1 * pw;
+            const int il = div_magic(p1, g.mg_ph), py = p1 - il * ph;
+            const int y = c.y0 + py - g.pad, x = c.x0 + px - g.pad, img = c.img0 + il;
+            const bool inside = idx < total && img < g.n && y >= 0 && y < g.h && x >= 0 && x < g.w;
+            const int8_t b = in[inside ? (((int64_t)img * g.h + y) * g.w + x) * g.c_in + ch : 0];
+            v[u] = inside ? (int)b : (idx < total ? g.pad_value : 0);
+        }
+    };
+    auto store_bytes = [&](unsigned char *P, int base, const int (&v)[4]) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * 256 + t;
+            if (idx < g.patch_bytes) P[idx] = (unsigned char)(int8_t)v[u];
+        }
+    };
 
-        // activation operands of all K steps (at most 4), gathered once per tile
-        v4i a[4][2];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks >= nsteps) break;
-            const int k16 = 2 * ks + half;
-            const int ti = k16 / u16, off = (k16 - ti * u16) << 4;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                // 16 bytes from an arbitrary byte address: five aligned dwords, funnel-shifted
-                const int addr = ti < g.kh ? pixbyte[i] + ti * pw * g.c_in + off : 0;
-                const int d = addr >> 2;
-                const unsigned sh = (unsigned)addr & 3u;
-                const unsigned w0 = P32[d], w1 = P32[d + 1], w2 = P32[d + 2], w3 = P32[d + 3], w4 = P32[d + 4];
-                a[ks][i][0] = (int)__builtin_amdgcn_alignbyte(w1, w0, sh);
-                a[ks][i][1] = (int)__builtin_amdgcn_alignbyte(w2, w1, sh);
-                a[ks][i][2] = (int)__builtin_amdgcn_alignbyte(w3, w2, sh);
-                a[ks][i][3] = (int)__builtin_amdgcn_alignbyte(w4, w3, sh);
+    int vn[4];
+    Item cur = decode(blockIdx.x < (unsigned)g.n_items ? (int)blockIdx.x : 0), prev = cur;
+    if (PIPE && (int)blockIdx.x < g.n_items) {
+        load_bytes(cur, 0, vn);
+        store_bytes(Pl, 0, vn);
+    }
+    int it = 0;
+    for (int item = blockIdx.x; item < g.n_items; item += gridDim.x, ++it) {
+        const unsigned char *Pc = Pl + (PIPE ? (it & 1) * g.patch_bytes : 0);
+        uint32_t *Oc = Ol + (it & 1) * (256 * BW);
+        if (it > 0) { prev = cur; cur = decode(item); }
+        const int next_item = item + (int)gridDim.x;
+        Item nxt = cur;
+        if (!PIPE) {
+            __syncthreads();      // previous item's patch fully consumed
+            for (int base = 0; base < g.patch_bytes; base += 256 * 4) {
+                int v[4];
+                load_bytes(cur, base, v);
+                store_bytes(Pl, base, v);
             }
         }
+        __syncthreads();          // patch (and, the first time, weights and start values) visible
+        if (PIPE && next_item < g.n_items) {
+            nxt = decode(next_item);
+            load_bytes(nxt, 0, vn);
+        }
+        if (ep.packed && it > 0)
+            conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), 256, o_blk >> 5, item_pos(prev), ep, t);
+        const unsigned *P32 = reinterpret_cast<const unsigned *>(Pc);
 
+        const TilePos pos = item_pos(cur);
+
+        // one 32-pixel tile after the other (keeps the register footprint small enough for
+        // three blocks per compute unit)
 #pragma unroll 1
-        for (int grp = 0; grp < NG; ++grp) {
-            // accumulators start at the channels' biases (see stage_bias_i32)
-            const int *Tg = Tl + grp * 64;
-            v16i acc[2][TN];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const v16i b16 = load_bias16<v16i>(Tg + j * 32, half);
-#pragma unroll
-                for (int i = 0; i < 2; ++i) acc[i][j] = b16;
-            }
+        for (int i = 0; i < 2; ++i) {
+            // activation operands of all K steps (at most 4), gathered once per pixel tile
+            const int pixb = i ? pixbyte[1] : pixbyte[0];
+            v4i a[4];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 if (ks >= nsteps) break;
+                const int k16 = 2 * ks + half;
+                const int ti = k16 / u16, off = (k16 - ti * u16) << 4;
+                // 16 bytes from an arbitrary byte address: five aligned dwords, funnel-shifted
+                const int addr = ti < g.kh ? pixb + ti * pw * g.c_in + off : 0;
+                const int d = addr >> 2;
+                const unsigned sh = (unsigned)addr & 3u;
+                const unsigned w0 = P32[d], w1 = P32[d + 1], w2 = P32[d + 2], w3 = P32[d + 3], w4 = P32[d + 4];
+                a[ks][0] = (int)__builtin_amdgcn_alignbyte(w1, w0, sh);
+                a[ks][1] = (int)__builtin_amdgcn_alignbyte(w2, w1, sh);
+                a[ks][2] = (int)__builtin_amdgcn_alignbyte(w3, w2, sh);
+                a[ks][3] = (int)__builtin_amdgcn_alignbyte(w4, w3, sh);
+            }
+            const int row0 = wave * 64 + i * 32;
+
+#pragma unroll 1
+            for (int grp = 0; grp < NG; ++grp) {
+                // accumulators start at the channels' biases (see stage_bias_i32)
+                const int *Tg = Tl + grp * 64;
+                v16i acc[TN];
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const v4i b = *reinterpret_cast<const v4i *>(Wl + ((grp * TN + j) * 32 + l32) * ws + ks * 32 + half * 16);
+                for (int j = 0; j < TN; ++j) acc[j] = load_bias16<v16i>(Tg + j * 32, half);
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a[ks][i], acc[i][j], 0, 0, 0);   // rows = channels
+                for (int ks = 0; ks < 4; ++ks) {
+                    if (ks >= nsteps) break;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const v4i b = *reinterpret_cast<const v4i *>(Wl + ((grp * TN + j) * 32 + l32) * ws + ks * 32 + half * 16);
+                        acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a[ks], acc[j], 0, 0, 0);   // rows = channels
+                    }
+                }
+                const int ch0 = o_blk + grp * 64;
+                if (ep.preact) {
+                    auto getx = [&](int, int j, int r) {
+                        return acc[j][r] - Tg[j * 32 + (r >> 2) * 8 + half * 4 + (r & 3)];
+                    };
+                    conv_tile_store_preact<1, TN>(getx, row0, ch0, l32, half, pos, ep.preact);
+                }
+                if (ep.packed) {
+                    // select this group's words without indexing the register array dynamically
+                    StepWords<TN> cursw = sw[0];
+#pragma unroll
+                    for (int q = 1; q < NG; ++q)
+                        if (grp == q) cursw = sw[q];
+                    auto gets = [&](int, int j, int r) { return acc[j][r]; };
+                    conv_tile_step_to_lds<1, TN>(gets, row0, grp * TN, BW, l32, half, cursw, ep.pool,
+                                                 ep.pool_first != 0, Oc);
                 }
             }
-            const int ch0 = o_blk + grp * 64;
-            if (ep.preact) {
-                auto getx = [&](int i, int j, int r) {
-                    return acc[i][j][r] - Tg[j * 32 + (r >> 2) * 8 + half * 4 + (r & 3)];
-                };
-                conv_tile_store_preact<2, TN>(getx, wave * 64, ch0, l32, half, pos, ep.preact);
-            }
-            if (ep.packed) {
-                // select this group's words without indexing the register array dynamically
-                StepWords<TN> cur = sw[0];
-#pragma unroll
-                for (int q = 1; q < NG; ++q)
-                    if (grp == q) cur = sw[q];
-                auto gets = [&](int i, int j, int r) { return acc[i][j][r]; };
-                conv_tile_step_to_lds<2, TN>(gets, wave * 64, grp * TN, BW, l32, half, cur, ep.pool,
-                                             ep.pool_first != 0, Ol);
-            }
         }
-        if (ep.packed) {
-            __syncthreads();
-            conv_tile_copy_out<BW>(Ol, 256, o_blk >> 5, pos, ep, t);
-        }
+        if (PIPE && next_item < g.n_items) store_bytes(Pl + ((it + 1) & 1) * g.patch_bytes, 0, vn);
+    }
+    if (ep.packed && it > 0) {
+        __syncthreads();
+        conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), 256, o_blk >> 5, item_pos(cur), ep, t);
     }
 }
 
@@ -411,14 +446,19 @@ template <int NG>
 bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, const EpiArgs &ep, hipStream_t s)
 {
     g.n_co_tiles = (g.c_out + 64 * NG - 1) / (64 * NG);
-    const size_t smem = (size_t)64 * NG * (g.kp + 16) + 256 * 2 * NG * 4 + 64 * NG * 4 + g.patch_bytes;
+    const bool pipe = g.patch_bytes <= 1024;
+    const size_t smem = (size_t)64 * NG * (g.kp + 16) + 2 * 256 * 2 * NG * 4 + 64 * NG * 4 +
+                        (size_t)(pipe ? 2 : 1) * g.patch_bytes;
     const int64_t items = (int64_t)g.tiles_x * g.tiles_y * ((g.n + g.ni - 1) / g.ni);
     if (smem > 64 * 1024 || items > 0x7fffffffLL || g.n_co_tiles > 65535) return BNN_ERR_UNSUPPORTED;
     g.n_items = (int)items;
     // persistent blocks: weights are staged once, then the block walks its share of the tiles
-    const int64_t cap = 256 * 2;
+    const int64_t cap = 256 * 3;
     const unsigned bx = (unsigned)(items < cap ? items : cap);
-    hipLaunchKernelGGL(conv_first_mfma<NG>, dim3(bx, (unsigned)g.n_co_tiles), dim3(256), smem, s, in, wt, g, ep);
+    if (pipe)
+        hipLaunchKernelGGL((conv_first_mfma<NG, true>), dim3(bx, (unsigned)g.n_co_tiles), dim3(256), smem, s, in, wt, g, ep);
+    else
+        hipLaunchKernelGGL((conv_first_mfma<NG, false>), dim3(bx, (unsigned)g.n_co_tiles), dim3(256), smem, s, in, wt, g, ep);
     return hip_result(hipGetLastError());
 }
 
