@@ -342,6 +342,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         if (ep.packed && it > 0)
             conv_tile_copy_out<BW>(Os + ((it - 1) & 1) * (64 * TM * BW), 64 * TM, o_blk >> 5, tile_pos(prev), ep, t);
 
+        __builtin_amdgcn_s_setprio(1);                        // the multiply phase outranks another wave's epilogue
         // accumulators start at the channels' biases (see stage_bias_f32)
         v16f acc[TM][TN];
 #pragma unroll
@@ -423,6 +424,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         }
 
         // ---- epilogue (shared with the first layer)
+        __builtin_amdgcn_s_setprio(0);
         const TilePos pos = tile_pos(cur);
         if (ep.preact) {
             auto getx = [&](int i, int j, int r) {
