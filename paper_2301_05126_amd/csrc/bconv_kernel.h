@@ -33,7 +33,9 @@ namespace {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int MAX_SMEM = 64 * 1024;
+// LDS per block: gfx950 has 160 KB per compute unit and lets one block take all of it; two
+// resident blocks per compute unit leave 80 KB each.
+constexpr int MAX_SMEM = 80 * 1024;
 
 template <int V> struct WordVec;
 template <> struct WordVec<4> { using type = uint4; };
@@ -85,6 +87,12 @@ __device__ __forceinline__ void lds_dma16(v4i rsrc, unsigned lds_base, unsigned 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
 }
+// the same with a scalar byte offset added to the address
+__device__ __forceinline__ void lds_dma4_soff(v4i rsrc, unsigned lds_base, unsigned voff, unsigned soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
 __device__ __forceinline__ void lds_dma4(v4i rsrc, unsigned lds_base, unsigned voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
@@ -100,15 +108,15 @@ __device__ __forceinline__ uint32_t expand_part(uint32_t w, int part, uint32_t s
 // Steps (one MFMA K-slice = one word per lane half) per weight chunk, by words per half.
 constexpr int steps_per_chunk(int wph) { return wph == 1 ? 9 : (wph == 2 ? 18 : (wph == 4 ? 12 : 8)); }
 
-// Whether a block keeps all of its weight chunks in LDS at once: up to 24 KB for any tile
-// (C_in <= 128), up to 48 KB for the 64-channel tile.
+// Whether a block keeps all of its weight chunks in LDS at once: up to 40 KB for any tile
+// (C_in <= 256 with 128 output channels), up to 48 KB for the 64-channel tile.
 constexpr bool weights_resident(int tm, int tn, int wph)
 {
-    const int v = wph >= 4 ? 4 : wph;
+    const int v = wph >= 2 ? 2 : wph;
     const int lsb = 2 * steps_per_chunk(wph) + v;
     const int nchunk = 9 * wph / steps_per_chunk(wph);
     const int bytes = nchunk * 64 * tn * lsb * 4;
-    return bytes <= 24 * 1024 || (tm * tn == 1 && bytes <= 48 * 1024);
+    return bytes <= 40 * 1024 || (tm * tn == 1 && bytes <= 48 * 1024);
 }
 
 struct TileCoord {
@@ -136,22 +144,31 @@ struct ConvGeom {
 // through registers (buffer_load ... lds; lanes outside the image or beyond the last image
 // address past the buffer's end and deliver zeros, i.e. -1 padding); with two patch buffers
 // the next tile's patch is in flight while the current tile is multiplied.
-template <int TM, int TN, int WPH>
+//
+// WDMA (wide layers whose weights are not resident; needs cw == 2*WPH words per pixel and
+// c_out a multiple of the block's channels): weight chunks also travel global -> LDS without
+// passing through registers, into two buffers that alternate; the chunk sequence is cyclic
+// over the tiles (weights do not depend on the tile), so the next chunk is always in flight
+// behind the current one and a chunk costs one barrier.  Rows are unpadded (16 words) and
+// their 8-byte units are stored at position unit ^ ((row >> 1) & 7), which keeps the 32 rows
+// read by one instruction on distinct banks.
+template <int TM, int TN, int WPH, bool WDMA = false>
 __global__ __launch_bounds__(256, 2)
 void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt, ConvGeom g, EpiArgs ep)
 {
     constexpr int BN = 64 * TN;
     constexpr int BW = 2 * TN;                         // packed output words per pixel of a block
     constexpr int CWP = 2 * WPH;                       // padded words per pixel
-    constexpr int V = WPH >= 4 ? 4 : WPH;              // words per LDS access
+    constexpr int V = WPH >= 2 ? 2 : WPH;              // words per LDS access
     constexpr int SPC = steps_per_chunk(WPH);
     constexpr int NCHUNK = 9 * WPH / SPC;
-    constexpr int LSB = 2 * SPC + V;                   // weight row stride (words); LSB/V is odd
+    constexpr int LSB = WDMA ? 2 * SPC : 2 * SPC + V;  // weight row stride (words); padded: LSB/V is odd
     constexpr int UPRW = 2 * SPC / V;                  // weight units per row per chunk
     constexpr int STG = (BN * UPRW + 255) / 256;       // weight units per thread per chunk
     constexpr int NVG = SPC / V;                       // V-step groups per chunk
-    constexpr bool RES = weights_resident(TM, TN, WPH);
-    constexpr int NBUF = RES ? NCHUNK : 1;
+    constexpr bool RES = !WDMA && weights_resident(TM, TN, WPH);
+    constexpr int NBUF = RES ? NCHUNK : (WDMA ? 2 : 1);
+    static_assert(!WDMA || (SPC == 8 && V == 2 && BN == 128), "weight DMA layout: 16-word rows, 128 rows");
     using vec_t = typename WordVec<V>::type;
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -247,6 +264,31 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         }
     }
 
+    // WDMA: instruction k (0..7) of this wave fills LDS words [(wave + 4k) * 64, +64) of a
+    // chunk buffer = rows 4*(wave + 4k) .. +3.  The word a lane delivers depends on k and on
+    // the chunk only through a scalar offset.
+    unsigned wd_voff = 0;
+    v4i wd_rsrc = make_raw_rsrc(wt, (unsigned)g.c_out * 9u * (unsigned)g.cw * 4u);
+    if (WDMA) {
+        const int phys = (lane & 15) >> 1, sub = lane & 1;
+        const int lw = ((phys ^ ((2 * wave + (lane >> 5)) & 7)) << 1) | sub;    // logical word of the chunk row
+        const int hh = lw >> 3, st = lw & 7;
+        wd_voff = (unsigned)(((o_blk + 4 * wave + (lane >> 4)) * 9 * g.cw + hh * WPH + st) * 4);
+    }
+    auto dma_w = [&](int chunk, int buf) {
+        const int s0 = chunk * SPC;
+        const unsigned soff0 = (unsigned)(((s0 / WPH) * g.cw + (s0 % WPH)) * 4);
+        const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) uint32_t *)(Bs + buf * BN * LSB) +
+                             (unsigned)__builtin_amdgcn_readfirstlane(wave) * 256u;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            lds_dma4_soff(wd_rsrc, dst + k * 1024u, wd_voff, soff0 + (unsigned)(k * 16 * 9 * 4) * (unsigned)g.cw);
+    };
+    // this lane's read offsets (words) inside a weight row, per V-step group
+    int wd_boff[NVG];
+#pragma unroll
+    for (int vg = 0; vg < NVG; ++vg) wd_boff[vg] = (((half * NVG + vg) ^ ((l32 >> 1) & 7)) << 1);
+
     // ---- patch fetch, global -> LDS directly.  Unit = 16 bytes (a whole-pixel multiple) when
     // the layer has exactly CWP words per pixel and CWP >= 4, else one word.
     const bool wide = (g.cw == CWP) && (CWP >= 4);
@@ -323,6 +365,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     };
 
     if (slot < g.n_ptiles) fetch_patch(next, 0);
+    if (WDMA && slot < g.n_ptiles) dma_w(0, 0);
+    int cc = 0;                                            // chunks done so far (WDMA buffer parity)
 
     // The packed words of a tile go to one of two LDS output tiles and are copied to global
     // memory after the next tile's barrier, so the stores drain while the next tile is
@@ -335,8 +379,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         prev = cur;
         cur = next;
         advance(next);
-        if (!RES) load_w(0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this tile's patch has landed
+        if (!RES && !WDMA) load_w(0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this tile's patch (and first weight chunk) has landed
         __syncthreads();                                      // ... for every wave; previous tile fully consumed
         if (g.dbuf && ptile + g.slots < g.n_ptiles) fetch_patch(next, buf ^ 1);
         if (ep.packed && it > 0)
@@ -353,13 +397,21 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         }
 
         for (int c = 0; c < NCHUNK; ++c) {
-            if (!RES) {
+            if (WDMA) {
+                if (c > 0) {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this chunk has landed
+                    __syncthreads();              // ... for every wave; previous chunk consumed
+                }
+                // next chunk of the cyclic sequence into the other buffer
+                if (c + 1 < NCHUNK || ptile + g.slots < g.n_ptiles) dma_w(c + 1 < NCHUNK ? c + 1 : 0, (cc + 1) & 1);
+            } else if (!RES) {
                 if (c > 0) __syncthreads();       // previous chunk consumed
                 store_w(0);
                 __syncthreads();
                 if (c + 1 < NCHUNK) load_w(c + 1);
             }
-            const uint32_t *Bc = RES ? Bs + c * BN * LSB : Bs;
+            const uint32_t *Bc = RES ? Bs + c * BN * LSB : (WDMA ? Bs + (cc & 1) * BN * LSB : Bs);
+            if (WDMA) ++cc;
 
             // raw words of V-step group vg: TM pixels' words and TN channels' words
             vec_t ra[2][TM], rb[2][TN];
@@ -372,7 +424,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                 for (int i = 0; i < TM; ++i) ra[slot2][i] = *reinterpret_cast<const vec_t *>(Pc + pixoff[i] + aoff);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    rb[slot2][j] = *reinterpret_cast<const vec_t *>(Bc + browoff + j * 32 * LSB + vg * V);
+                    rb[slot2][j] = *reinterpret_cast<const vec_t *>(
+                        WDMA ? Bc + (wn * TN * 32 + j * 32 + l32) * LSB + wd_boff[vg] : Bc + browoff + j * 32 * LSB + vg * V);
             };
             load_group(0, 0);
             v8i a[2][TM], b[2][TN];
@@ -449,12 +502,16 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     }
 }
 
-template <int TM, int TN, int WPH>
+template <int TM, int TN, int WPH, bool WDMA>
 bool make_geom(int n, int h, int w, int c_in, int c_out, ConvGeom &g, size_t &smem)
 {
-    constexpr int V = WPH >= 4 ? 4 : WPH;
-    constexpr int LSB = 2 * steps_per_chunk(WPH) + V;
-    constexpr int NBUF = weights_resident(TM, TN, WPH) ? 9 * WPH / steps_per_chunk(WPH) : 1;
+    constexpr int V = WPH >= 2 ? 2 : WPH;
+    constexpr int LSB = WDMA ? 2 * steps_per_chunk(WPH) : 2 * steps_per_chunk(WPH) + V;
+    constexpr int NBUF = WDMA ? 2 : (weights_resident(TM, TN, WPH) ? 9 * WPH / steps_per_chunk(WPH) : 1);
+    // weights by DMA: exact channel words, whole channel tiles, byte offsets below 2^31
+    if (WDMA && ((c_in + 31) / 32 != 2 * WPH || c_out % (64 * TN) != 0 ||
+                 (int64_t)c_out * 9 * ((c_in + 31) / 32) * 4 >= 0x7fffffffLL))
+        return false;
     g.n = n; g.h = h; g.w = w;
     g.cw = (c_in + 31) / 32;
     g.c_out = c_out;
@@ -483,26 +540,35 @@ bool make_geom(int n, int h, int w, int c_in, int c_out, ConvGeom &g, size_t &sm
     return smem <= (size_t)MAX_SMEM;
 }
 
-template <int TM, int TN, int WPH>
+template <int TM, int TN, int WPH, bool WDMA = false>
 bnn_status launch_one(const uint32_t *in, const uint32_t *wt, int n, int h, int w, int c_in, int c_out,
                       const EpiArgs &ep, hipStream_t s)
 {
     ConvGeom g;
     size_t smem;
-    if (!make_geom<TM, TN, WPH>(n, h, w, c_in, c_out, g, smem)) return BNN_ERR_UNSUPPORTED;
+    if (!make_geom<TM, TN, WPH, WDMA>(n, h, w, c_in, c_out, g, smem)) return BNN_ERR_UNSUPPORTED;
     const unsigned blocks = (unsigned)(g.slots * g.n_co_tiles);
-    hipLaunchKernelGGL((bconv_mfma<TM, TN, WPH>), dim3(blocks), dim3(256), smem, s, in, wt, g, ep);
+    if (smem > 64 * 1024) {          // above the default limit of dynamic LDS: opt in once
+        static bool raised = false;
+        if (!raised) {
+            const bnn_status e = hip_result(hipFuncSetAttribute((const void *)bconv_mfma<TM, TN, WPH, WDMA>,
+                                                                hipFuncAttributeMaxDynamicSharedMemorySize, MAX_SMEM));
+            if (e != BNN_OK) return e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL((bconv_mfma<TM, TN, WPH, WDMA>), dim3(blocks), dim3(256), smem, s, in, wt, g, ep);
     return hip_result(hipGetLastError());
 }
 
 // Work items (pixel tiles x channel tiles) a (64*TM pixels) x (64*TN channels) block tile
 // would give, or -1 if its LDS footprint does not fit.
-template <int TM, int TN, int WPH>
+template <int TM, int TN, int WPH, bool WDMA = false>
 int64_t blocks_one(int n, int h, int w, int c_in, int c_out)
 {
     ConvGeom g;
     size_t smem;
-    if (!make_geom<TM, TN, WPH>(n, h, w, c_in, c_out, g, smem)) return -1;
+    if (!make_geom<TM, TN, WPH, WDMA>(n, h, w, c_in, c_out, g, smem)) return -1;
     return (int64_t)g.n_co_tiles * g.n_ptiles;
 }
 
@@ -512,8 +578,10 @@ bnn_status launch_wph(const uint32_t *in, const uint32_t *wt, int n, int h, int 
                       const EpiArgs &ep, hipStream_t s)
 {
     const int64_t want = 512;     // two resident blocks per compute unit
-    if (blocks_one<4, 2, WPH>(n, h, w, c_in, c_out) >= want)
-        return launch_one<4, 2, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
+    // the largest tile keeps its weights resident (WPH <= 4) or streams them by DMA
+    constexpr bool WD = WPH >= 8;
+    if (blocks_one<4, 2, WPH, WD>(n, h, w, c_in, c_out) >= want)
+        return launch_one<4, 2, WPH, WD>(in, wt, n, h, w, c_in, c_out, ep, s);
     if (blocks_one<2, 2, WPH>(n, h, w, c_in, c_out) >= want)
         return launch_one<2, 2, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
     return launch_one<1, 1, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);

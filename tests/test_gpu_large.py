@@ -148,3 +148,29 @@ def test_conv_sweep_batch1024_sampled_images(hw, c):
     np.testing.assert_array_equal(got[idx], want)
     # the other images: bits look random, none of the fill value survives
     assert not np.any(np.all(got.reshape(n, -1) == 0xFFFFFFFF, axis=1))
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("n,hw,ci,co,pool", [(8192, 4, 1024, 128, 2), (2048, 8, 512, 256, 1), (2050, 8, 512, 128, 2)])
+def test_conv_wide_layers_streamed_weights_sampled_images(n, hw, ci, co, pool):
+    """C_in >= 512 at a batch that selects the largest block tile (weight chunks streamed through two
+    LDS buffers): sampled images against the oracle, first / last / ragged-tail images included."""
+    cw = ci // 32
+    rng = W.rng_for(4, hw + 50, ci % 1000 + co)
+    print(f"conv wide {hw}x{hw} {ci}->{co} batch {n} pool {pool}", flush=True)
+    xw = rng.integers(0, 2**32, size=(n, hw, hw, cw), dtype=np.uint32)
+    wt = W.draw_pm1(rng, (co, 3, 3, ci))
+    thr = W.draw_threshold(rng, co, 9 * ci)
+    flip = W.draw_flip(rng, co)
+    wd = dev(pack_pm1(wt.reshape(co * 9, ci)).reshape(co, 3, 3, cw))
+    out = fill_i32((n, hw // pool, hw // pool, co // 32), -1)
+    P.bnn_conv_binary(dev(xw), n, hw, hw, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=pool, packed_out=out)
+    torch.cuda.synchronize()
+    got = host_u32(out)
+    idx = np.array([0, 1, 15, 16, n // 2 + 3, n - 17, n - 2, n - 1])
+    x_s = unpack_words(xw[idx], ci)
+    s = oracle.step(oracle.conv2d(x_s, wt, 1, -1), thr, flip)
+    if pool == 2:
+        s = oracle.maxpool2(s)
+    np.testing.assert_array_equal(got[idx], pack_pm1(s))
+    assert not np.any(np.all(got.reshape(n, -1) == 0xFFFFFFFF, axis=1))
