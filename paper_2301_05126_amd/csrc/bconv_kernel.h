@@ -25,12 +25,12 @@
 #define BNN_BCONV_KERNEL_H
 #include "bnn_internal.h"
 #include "conv_epilogue.h"
+#include "lds_dma.h"
 
 namespace bnn {
 
 namespace {
 
-typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 // LDS per block: gfx950 has 160 KB per compute unit and lets one block take all of it; two
@@ -49,61 +49,6 @@ __device__ __forceinline__ uint32_t vec_word(const uint32_t &v, int) { return v;
 __device__ __forceinline__ void vec_set(uint4 &v, int q, uint32_t x) { if (q == 0) v.x = x; else if (q == 1) v.y = x; else if (q == 2) v.z = x; else v.w = x; }
 __device__ __forceinline__ void vec_set(uint2 &v, int q, uint32_t x) { if (q == 0) v.x = x; else v.y = x; }
 __device__ __forceinline__ void vec_set(uint32_t &v, int, uint32_t x) { v = x; }
-
-// 32 packed bits -> 32 FP4 values (0b0010 = +1.0, 0b1010 = -1.0) in the low four dwords of an
-// MFMA operand; sgn / one hold 0x88888888 / 0x22222222 in registers (one v_and_or_b32 each).
-__device__ __forceinline__ v8i expand_fp4(uint32_t w, uint32_t sgn, uint32_t one)
-{
-    v8i r;
-    r[0] = (int)(((w << 3) & sgn) | one);
-    r[1] = (int)(((w << 2) & sgn) | one);
-    r[2] = (int)(((w << 1) & sgn) | one);
-    r[3] = (int)((w & sgn) | one);
-    r[4] = 0; r[5] = 0; r[6] = 0; r[7] = 0;
-    return r;
-}
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-
-// Buffer resource over `bytes` bytes at `base` (raw buffer, offsets past the end read zeros).
-__device__ __forceinline__ v4i make_raw_rsrc(const void *base, unsigned bytes)
-{
-    const unsigned long long a = (unsigned long long)base;
-    v4i r;
-    r[0] = (int)(unsigned)a;
-    r[1] = (int)(unsigned)((a >> 32) & 0xffffu);       // stride 0
-    r[2] = (int)bytes;
-    r[3] = 0x00020000;
-    return r;
-}
-
-// One wave-wide copy global -> LDS without touching vector registers: lane l's 16 (or 4)
-// bytes at byte offset voff of the buffer land at LDS byte address lds_base + 16*l (4*l).
-// Written as inline assembly so that the compiler does not serialise the transfer against
-// the LDS reads of the tile being multiplied; completion is awaited explicitly
-// (s_waitcnt vmcnt(0)) before the barrier that publishes the buffer.  lds_base is wave-uniform.
-__device__ __forceinline__ void lds_dma16(v4i rsrc, unsigned lds_base, unsigned voff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
-}
-// the same with a scalar byte offset added to the address
-__device__ __forceinline__ void lds_dma4_soff(v4i rsrc, unsigned lds_base, unsigned voff, unsigned soff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
-}
-__device__ __forceinline__ void lds_dma4(v4i rsrc, unsigned lds_base, unsigned voff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
-}
-
-// Dword `part` (0..3) of expand_fp4.
-__device__ __forceinline__ uint32_t expand_part(uint32_t w, int part, uint32_t sgn, uint32_t one)
-{
-    return part == 3 ? ((w & sgn) | one) : (((w << (3 - part)) & sgn) | one);
-}
 
 // Steps (one MFMA K-slice = one word per lane half) per weight chunk, by words per half.
 constexpr int steps_per_chunk(int wph) { return wph == 1 ? 9 : (wph == 2 ? 18 : (wph == 4 ? 12 : 8)); }
