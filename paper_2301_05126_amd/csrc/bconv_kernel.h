@@ -527,6 +527,8 @@ bnn_status launch_wph(const uint32_t *in, const uint32_t *wt, int n, int h, int 
     constexpr bool WD = WPH >= 8;
     if (blocks_one<4, 2, WPH, WD>(n, h, w, c_in, c_out) >= want)
         return launch_one<4, 2, WPH, WD>(in, wt, n, h, w, c_in, c_out, ep, s);
+    if (WD && blocks_one<2, 2, WPH, WD>(n, h, w, c_in, c_out) >= want)
+        return launch_one<2, 2, WPH, WD>(in, wt, n, h, w, c_in, c_out, ep, s);
     if (blocks_one<2, 2, WPH>(n, h, w, c_in, c_out) >= want)
         return launch_one<2, 2, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
     return launch_one<1, 1, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
