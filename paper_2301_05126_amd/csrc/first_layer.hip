@@ -251,19 +251,27 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
     stage_bias_i32(ep, o_blk, 64 * NG, g.c_out, 1 << 30, Tl, t);
 
     // ---- persistent loop over (image group, tile) work items
-    struct Item { int img0, y0, x0; };
+    struct Item { int grp, ty, tx; };                   // image group, tile row, tile column
     auto decode = [&](int item) {
         Item c;
         int rest = item;
-        const int tile_x = rest % g.tiles_x; rest /= g.tiles_x;
-        const int tile_y = rest % g.tiles_y; rest /= g.tiles_y;
-        c.img0 = rest * g.ni; c.y0 = tile_y * th; c.x0 = tile_x * tw;
+        c.tx = rest % g.tiles_x; rest /= g.tiles_x;
+        c.ty = rest % g.tiles_y; c.grp = rest / g.tiles_y;
         return c;
+    };
+    // a step of gridDim.x items is a fixed (group, row, column) increment with carries
+    const Item step = decode((int)gridDim.x);
+    auto advance = [&](Item &c) {
+        c.tx += step.tx;
+        if (c.tx >= g.tiles_x) { c.tx -= g.tiles_x; ++c.ty; }
+        c.ty += step.ty;
+        if (c.ty >= g.tiles_y) { c.ty -= g.tiles_y; ++c.grp; }
+        c.grp += step.grp;
     };
     auto item_pos = [&](const Item &c) {
         TilePos pos;
         pos.n = g.n; pos.h = g.ho; pos.w = g.wo; pos.c_out = g.c_out;
-        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = c.img0; pos.y0 = c.y0; pos.x0 = c.x0;
+        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = c.grp * g.ni; pos.y0 = c.ty * th; pos.x0 = c.tx * tw;
         return pos;
     };
     // Patch bytes base + u*256 + t (u = 0..3) of an item: pad_value outside the image, zero in
@@ -271,16 +279,45 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
     // bytes that are not read from the image load the tensor's first byte instead.
     const int total = g.ni * ph * pw * g.c_in;
     auto load_bytes = [&](const Item &c, int base, int (&v)[4]) {
+        const int img0 = c.grp * g.ni, y0 = c.ty * th, x0 = c.tx * tw;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int idx = base + u * 256 + t;
             const int p0 = div_magic(idx, g.mg_cin), ch = idx - p0 * g.c_in;
             const int p1 = div_magic(p0, g.mg_pw), px = p0 - p1 * pw;
             const int il = div_magic(p1, g.mg_ph), py = p1 - il * ph;
-            const int y = c.y0 + py - g.pad, x = c.x0 + px - g.pad, img = c.img0 + il;
+            const int y = y0 + py - g.pad, x = x0 + px - g.pad, img = img0 + il;
             const bool inside = idx < total && img < g.n && y >= 0 && y < g.h && x >= 0 && x < g.w;
             const int8_t b = in[inside ? (((int64_t)img * g.h + y) * g.w + x) * g.c_in + ch : 0];
             v[u] = inside ? (int)b : (idx < total ? g.pad_value : 0);
+        }
+    };
+    // PIPE: the position of a thread's four bytes inside the patch does not depend on the
+    // item, so it is worked out once: image, row and column relative to the tile origin
+    // (packed into one register) and the byte offset relative to the origin's address.
+    int pk[4], rel[4];
+    if (PIPE) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = u * 256 + t;
+            const int p0 = div_magic(idx, g.mg_cin), ch = idx - p0 * g.c_in;
+            const int p1 = div_magic(p0, g.mg_pw), px = p0 - p1 * pw;
+            const int il = div_magic(p1, g.mg_ph), py = p1 - il * ph;
+            const int ry = py - g.pad, rx = px - g.pad;           // small: fit signed bytes
+            pk[u] = idx < total ? ((il << 16) | ((ry & 0xff) << 8) | (rx & 0xff)) : -1;
+            rel[u] = ((il * g.h + ry) * g.w + rx) * g.c_in + ch;
+        }
+    }
+    auto load_bytes_pipe = [&](const Item &c, int (&v)[4]) {
+        const int img0 = c.grp * g.ni, y0 = c.ty * th, x0 = c.tx * tw;
+        const int8_t *origin = in + (((int64_t)img0 * g.h + y0) * g.w + x0) * g.c_in;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int y = y0 + (int)(int8_t)(pk[u] >> 8), x = x0 + (int)(int8_t)pk[u], img = img0 + (pk[u] >> 16);
+            const bool in_patch = pk[u] >= 0;
+            const bool inside = in_patch & (img < g.n) & ((unsigned)y < (unsigned)g.h) & ((unsigned)x < (unsigned)g.w);
+            const int8_t b = inside ? origin[rel[u]] : in[0];
+            v[u] = inside ? (int)b : (in_patch ? g.pad_value : 0);
         }
     };
     auto store_bytes = [&](unsigned char *P, int base, const int (&v)[4]) {
@@ -292,18 +329,19 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
     };
 
     int vn[4];
-    Item cur = decode(blockIdx.x < (unsigned)g.n_items ? (int)blockIdx.x : 0), prev = cur;
+    Item cur = decode(blockIdx.x < (unsigned)g.n_items ? (int)blockIdx.x : 0), prev = cur, nxt = cur;
     if (PIPE && (int)blockIdx.x < g.n_items) {
-        load_bytes(cur, 0, vn);
+        load_bytes_pipe(cur, vn);
         store_bytes(Pl, 0, vn);
     }
     int it = 0;
     for (int item = blockIdx.x; item < g.n_items; item += gridDim.x, ++it) {
         const unsigned char *Pc = Pl + (PIPE ? (it & 1) * g.patch_bytes : 0);
         uint32_t *Oc = Ol + (it & 1) * (256 * BW);
-        if (it > 0) { prev = cur; cur = decode(item); }
+        prev = cur;
+        cur = nxt;
+        advance(nxt);
         const int next_item = item + (int)gridDim.x;
-        Item nxt = cur;
         if (!PIPE) {
             __syncthreads();      // previous item's patch fully consumed
             for (int base = 0; base < g.patch_bytes; base += 256 * 4) {
@@ -313,10 +351,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
             }
         }
         __syncthreads();          // patch (and, the first time, weights and start values) visible
-        if (PIPE && next_item < g.n_items) {
-            nxt = decode(next_item);
-            load_bytes(nxt, 0, vn);
-        }
+        if (PIPE && next_item < g.n_items) load_bytes_pipe(nxt, vn);
         if (ep.packed && it > 0)
             conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), 256, o_blk >> 5, item_pos(prev), ep, t);
         const unsigned *P32 = reinterpret_cast<const unsigned *>(Pc);
