@@ -384,6 +384,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
 
 #pragma unroll 1
             for (int grp = 0; grp < NG; ++grp) {
+                __builtin_amdgcn_s_setprio(1);           // multiplies outrank other waves' epilogues
                 // accumulators start at the channels' biases (see stage_bias_i32)
                 const int *Tg = Tl + grp * 64;
                 v16i acc[TN];
@@ -398,6 +399,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
                         acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a[ks], acc[j], 0, 0, 0);   // rows = channels
                     }
                 }
+                __builtin_amdgcn_s_setprio(0);
                 const int ch0 = o_blk + grp * 64;
                 if (ep.preact) {
                     auto getx = [&](int, int j, int r) {
