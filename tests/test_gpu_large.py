@@ -152,7 +152,8 @@ def test_conv_sweep_batch1024_sampled_images(hw, c):
 
 @pytest.mark.timeout(300)
 @pytest.mark.parametrize("n,hw,ci,co,pool", [(8192, 4, 1024, 128, 2), (2048, 8, 512, 256, 1), (2050, 8, 512, 128, 2),
-                                             (4096, 4, 1024, 128, 1), (1030, 8, 512, 128, 2)])
+                                             (4096, 4, 1024, 128, 1), (1030, 8, 512, 128, 2), (3001, 5, 512, 256, 1),
+                                             (2100, 7, 1024, 128, 1)])
 def test_conv_wide_layers_streamed_weights_sampled_images(n, hw, ci, co, pool):
     """C_in >= 512 at a batch that selects the largest block tile (weight chunks streamed through two
     LDS buffers): sampled images against the oracle, first / last / ragged-tail images included."""
