@@ -114,6 +114,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     constexpr bool RES = !WDMA && weights_resident(TM, TN, WPH);
     constexpr int NBUF = RES ? NCHUNK : (WDMA ? 2 : 1);
     static_assert(!WDMA || (SPC == 8 && V == 2 && BN == 128), "weight DMA layout: 16-word rows, 128 rows");
+    static_assert(NCHUNK == 1 || (SPC % 2 == 0 && NVG % 2 == 0), "operand pipeline across chunks: buffer parity");
     using vec_t = typename WordVec<V>::type;
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -341,6 +342,49 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
             for (int i = 0; i < TM; ++i) acc[i][j] = b16;
         }
 
+        // Raw words of a V-step group (TM pixels' words, TN channels' words) and the expanded
+        // operands of the current and the next MFMA step.  The pipeline "read words, expand
+        // them, multiply" runs across chunk borders where the data allows it (XA: pixel words
+        // always, the patch is resident; XB: channel words only when the weights are resident).
+        constexpr bool XA = RES || WDMA, XB = RES;
+        vec_t ra[2][TM], rb[2][TN];
+        v8i a[2][TM], b[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int q = 4; q < 8; ++q) a[0][i][q] = a[1][i][q] = 0;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 4; q < 8; ++q) b[0][j][q] = b[1][j][q] = 0;
+        auto load_a = [&](int c, int vg, int slot2) {
+            const int s = c * SPC + vg * V;
+            const int tap = s / WPH, cwi = s % WPH;
+            const int ti = tap / 3, tj = tap - ti * 3;
+            const int aoff = (ti * pw + tj) * CWP + cwi;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) ra[slot2][i] = *reinterpret_cast<const vec_t *>(Pc + pixoff[i] + aoff);
+        };
+        auto load_b = [&](const uint32_t *Bc, int vg, int slot2) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                rb[slot2][j] = *reinterpret_cast<const vec_t *>(
+                    WDMA ? Bc + (wn * TN * 32 + j * 32 + l32) * LSB + wd_boff[vg] : Bc + browoff + j * 32 * LSB + vg * V);
+        };
+        if (XA) {                                           // pixel operands of the tile's first step
+            load_a(0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const v8i e = expand_fp4(vec_word(ra[0][i], 0), sgn, one);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a[0][i][q] = e[q];
+            }
+        }
+
+        // resident weights: the chunk loop is unrolled too (straight-line code keeps the operand
+        // pipeline in registers without copies)
+        constexpr int CUNROLL = RES ? NCHUNK : 1;
+#pragma unroll CUNROLL
         for (int c = 0; c < NCHUNK; ++c) {
             if (WDMA) {
                 if (c > 0) {
@@ -356,64 +400,65 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                 if (c + 1 < NCHUNK) load_w(c + 1);
             }
             const uint32_t *Bc = RES ? Bs + c * BN * LSB : (WDMA ? Bs + (cc & 1) * BN * LSB : Bs);
+            const uint32_t *Bn = Bc + BN * LSB;            // next chunk's weights (resident weights only)
             if (WDMA) ++cc;
+            const bool more = c + 1 < NCHUNK;
 
-            // raw words of V-step group vg: TM pixels' words and TN channels' words
-            vec_t ra[2][TM], rb[2][TN];
-            auto load_group = [&](int vg, int slot2) {
-                const int s = c * SPC + vg * V;
-                const int tap = s / WPH, cwi = s % WPH;
-                const int ti = tap / 3, tj = tap - ti * 3;
-                const int aoff = (ti * pw + tj) * CWP + cwi;
+            // operands of the chunk's first step that did not come from the previous chunk
+            if (!XA) {
+                load_a(c, 0, 0);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) ra[slot2][i] = *reinterpret_cast<const vec_t *>(Pc + pixoff[i] + aoff);
+                for (int i = 0; i < TM; ++i) {
+                    const v8i e = expand_fp4(vec_word(ra[0][i], 0), sgn, one);
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    rb[slot2][j] = *reinterpret_cast<const vec_t *>(
-                        WDMA ? Bc + (wn * TN * 32 + j * 32 + l32) * LSB + wd_boff[vg] : Bc + browoff + j * 32 * LSB + vg * V);
-            };
-            load_group(0, 0);
-            v8i a[2][TM], b[2][TN];
+                    for (int q = 0; q < 4; ++q) a[0][i][q] = e[q];
+                }
+            }
+            if (!XB || c == 0) {
+                load_b(Bc, 0, 0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[0][i] = expand_fp4(vec_word(ra[0][i], 0), sgn, one);
+                for (int j = 0; j < TN; ++j) {
+                    const v8i e = expand_fp4(vec_word(rb[0][j], 0), sgn, one);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[0][j] = expand_fp4(vec_word(rb[0][j], 0), sgn, one);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int q = 4; q < 8; ++q) a[1][i][q] = 0;
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int q = 4; q < 8; ++q) b[1][j][q] = 0;
+                    for (int q = 0; q < 4; ++q) b[0][j][q] = e[q];
+                }
+            }
             // The instruction order below is the issue order (scheduling barriers pin it): the
             // LDS reads of the next word group, then each MFMA followed by its share of the
             // next step's operand dwords, so that VALU work runs in the shadow of the MFMAs.
 #pragma unroll
             for (int st = 0; st < SPC; ++st) {
-                const int cur = st & 1, nxt = cur ^ 1;
+                const int cur_s = st & 1, nxt = cur_s ^ 1;
                 const int vg = st / V, q = st % V;
-                if (q == 0 && vg + 1 < NVG) {
-                    load_group(vg + 1, (vg + 1) & 1);
+                const bool last_group = vg + 1 == NVG;
+                if (q == 0) {
+                    if (!last_group) {
+                        load_a(c, vg + 1, (vg + 1) & 1);
+                        load_b(Bc, vg + 1, (vg + 1) & 1);
+                    } else if (more) {                    // first group of the next chunk
+                        if (XA) load_a(c + 1, 0, 0);
+                        if (XB) load_b(Bn, 0, 0);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                const int vg1 = (st + 1) / V, q1 = (st + 1) % V;
+                const bool in_chunk = st + 1 < SPC;
+                const int vg1 = in_chunk ? (st + 1) / V : 0, q1 = in_chunk ? (st + 1) % V : 0;
+                const bool next_a = in_chunk || (XA && more), next_b = in_chunk || (XB && more);
 #pragma unroll
                 for (int k = 0; k < TM * TN; ++k) {
                     const int i = k / TN, j = k % TN;
                     // weights first: accumulator rows = channels, columns (lanes) = pixels
                     // (zero scale operands select the instruction form without block scales)
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        b[cur][j], a[cur][i], acc[i][j], 4, 4, 0, 0, 0, 0);
-                    if (st + 1 < SPC) {
+                        b[cur_s][j], a[cur_s][i], acc[i][j], 4, 4, 0, 0, 0, 0);
 #pragma unroll
-                        for (int d = k * DPM; d < (k + 1) * DPM && d < 4 * (TM + TN); ++d) {
-                            const int wi = d >> 2, part = d & 3;
-                            if (wi < TM)
-                                a[nxt][wi][part] = (int)expand_part(vec_word(ra[vg1 & 1][wi], q1), part, sgn, one);
-                            else
-                                b[nxt][wi - TM][part] =
-                                    (int)expand_part(vec_word(rb[vg1 & 1][wi - TM], q1), part, sgn, one);
+                    for (int d = k * DPM; d < (k + 1) * DPM && d < 4 * (TM + TN); ++d) {
+                        const int wi = d >> 2, part = d & 3;
+                        if (wi < TM) {
+                            if (next_a) a[nxt][wi][part] = (int)expand_part(vec_word(ra[vg1 & 1][wi], q1), part, sgn, one);
+                        } else {
+                            if (next_b)
+                                b[nxt][wi - TM][part] = (int)expand_part(vec_word(rb[vg1 & 1][wi - TM], q1), part, sgn, one);
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
