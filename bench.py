@@ -87,7 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="vgg_small_b4096", choices=sorted(WORKLOADS))
     ap.add_argument("--no-extras", action="store_true", help="skip sweeps / latency / CPU baseline")
-    ap.add_argument("--cpu-images", type=int, default=160, help="images in the CPU-oracle sample")
+    ap.add_argument("--cpu-images", type=int, default=640,
+                    help="images in the CPU-oracle sample (640 images of the default workload are about 12 s of host work)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
