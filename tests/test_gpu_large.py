@@ -153,19 +153,21 @@ def test_conv_sweep_batch1024_sampled_images(hw, c):
 @pytest.mark.timeout(300)
 @pytest.mark.parametrize("n,hw,ci,co,pool", [(8192, 4, 1024, 128, 2), (2048, 8, 512, 256, 1), (2050, 8, 512, 128, 2),
                                              (4096, 4, 1024, 128, 1), (1030, 8, 512, 128, 2), (3001, 5, 512, 256, 1),
-                                             (2100, 7, 1024, 128, 1)])
+                                             (2100, 7, 1024, 128, 1), (1024, 8, 512, 192, 2), (1500, 6, 608, 160, 1)])
 def test_conv_wide_layers_streamed_weights_sampled_images(n, hw, ci, co, pool):
     """C_in >= 512 at a batch that selects the largest block tile (weight chunks streamed through two
     LDS buffers): sampled images against the oracle, first / last / ragged-tail images included."""
-    cw = ci // 32
+    cw = (ci + 31) // 32
     rng = W.rng_for(4, hw + 50, ci % 1000 + co)
     print(f"conv wide {hw}x{hw} {ci}->{co} batch {n} pool {pool}", flush=True)
     xw = rng.integers(0, 2**32, size=(n, hw, hw, cw), dtype=np.uint32)
+    if ci % 32:
+        xw[..., -1] &= np.uint32((1 << (ci % 32)) - 1)       # tail bits of the last word are zero
     wt = W.draw_pm1(rng, (co, 3, 3, ci))
     thr = W.draw_threshold(rng, co, 9 * ci)
     flip = W.draw_flip(rng, co)
     wd = dev(pack_pm1(wt.reshape(co * 9, ci)).reshape(co, 3, 3, cw))
-    out = fill_i32((n, hw // pool, hw // pool, co // 32), -1)
+    out = fill_i32((n, hw // pool, hw // pool, (co + 31) // 32), -1)
     P.bnn_conv_binary(dev(xw), n, hw, hw, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=pool, packed_out=out)
     torch.cuda.synchronize()
     got = host_u32(out)
