@@ -202,25 +202,48 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
             }
     }
     if (ep.packed) {
+        // A ballot over the 32 columns of a tile is the packed word of one row (one per lane
+        // half).  Lane r of each half keeps the word of register r, so that a tile's 32 words
+        // leave with one store instruction per row block instead of one per word.
         const int64_t nw = (N + 31) >> 5;
+        int thr[TN];
+        bool flip[TN], cok[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int64_t col = cbase + j * 32;
-            const bool cok = col < N;
-            const int thr = cok ? ep.thr[col] : 0;
-            const bool flip = cok && ep.flip && ep.flip[col];
-            const int64_t wi = (n0 + wn * TN * 32 + j * 32) >> 5;
+            cok[j] = col < N;
+            thr[j] = cok[j] ? ep.thr[col] : 0;
+            flip[j] = cok[j] && ep.flip && ep.flip[col];
+        }
+        const int64_t wi0 = (n0 + wn * TN * 32) >> 5;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) {
+            unsigned mine[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                mine[j] = 0;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int x = (int)acc[i][j][r] - corr;
-                    const bool bit = cok && ((x > thr) != flip);
+                    const bool bit = cok[j] && ((x > thr[j]) != flip[j]);
                     const unsigned long long mask = __ballot(bit);
                     const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
-                    const int64_t row = rbase + i * 32 + (r >> 2) * 8 + (r & 3);
-                    if (l32 == 0 && row < M && wi < nw) ep.packed[row * nw + wi] = word;
+                    if (l32 == r) mine[j] = word;
                 }
+            }
+            const int64_t row = rbase + i * 32 + (l32 >> 2) * 8 + (l32 & 3);
+            if (l32 < 16 && row < M) {
+                uint32_t *dst = ep.packed + row * nw + wi0;
+                if (TN == 2 && (nw & 1) == 0 && wi0 + 1 < nw) {
+                    *reinterpret_cast<uint2 *>(dst) = make_uint2(mine[0], mine[TN - 1]);
+                } else if (TN == 4 && (nw & 3) == 0 && wi0 + 3 < nw) {
+                    *reinterpret_cast<uint4 *>(dst) = make_uint4(mine[0], mine[1 % TN], mine[2 % TN], mine[3 % TN]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        if (wi0 + j < nw) dst[j] = mine[j];
+                }
+            }
         }
     }
 }
