@@ -14,7 +14,10 @@ LIB = os.path.join(PKG, "libbnn.so")
 UNITS = [("bnn_api.hip", [], "bnn_api.o"), ("bgemm.hip", [], "bgemm.o"), ("bconv.hip", [], "bconv.o"),
          ("first_layer.hip", [], "first_layer.o"), ("elementwise.hip", [], "elementwise.o"),
          ("host_tools.hip", [], "host_tools.o")]
-UNITS += [("bconv_inst.hip", [f"-DBNN_CONV_WPH={w}"], f"bconv_wph{w}.o") for w in (1, 2, 4, 8, 16)]
+# the convolution kernels: per channel-word width, the 256 x 128 tile (part 1, slowest) apart
+UNITS = [("bconv_inst.hip", [f"-DBNN_CONV_WPH={w}", "-DBNN_CONV_PART=1"], f"bconv_wph{w}_big.o")
+         for w in (4, 2, 16, 8, 1)] + UNITS
+UNITS += [("bconv_inst.hip", [f"-DBNN_CONV_WPH={w}", "-DBNN_CONV_PART=0"], f"bconv_wph{w}.o") for w in (1, 2, 4, 8, 16)]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

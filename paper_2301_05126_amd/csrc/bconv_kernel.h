@@ -563,6 +563,16 @@ int64_t blocks_one(int n, int h, int w, int c_in, int c_out)
 }
 
 // Largest block tile that fits LDS and still fills most of the 256 compute units.
+}  // namespace
+
+// The 256 x 128 tile of a channel width is compiled in a translation unit of its own (it is the
+// slowest to build); the dispatcher below reaches it through this function.
+template <int WPH>
+bnn_status launch_conv_big_tile(const uint32_t *in, const uint32_t *wt, int n, int h, int w, int c_in,
+                                int c_out, const EpiArgs &ep, hipStream_t s);
+
+namespace {
+
 template <int WPH>
 bnn_status launch_wph(const uint32_t *in, const uint32_t *wt, int n, int h, int w, int c_in, int c_out,
                       const EpiArgs &ep, hipStream_t s)
@@ -571,7 +581,7 @@ bnn_status launch_wph(const uint32_t *in, const uint32_t *wt, int n, int h, int 
     // the largest tile keeps its weights resident (WPH <= 4) or streams them by DMA
     constexpr bool WD = WPH >= 8;
     if (blocks_one<4, 2, WPH, WD>(n, h, w, c_in, c_out) >= want)
-        return launch_one<4, 2, WPH, WD>(in, wt, n, h, w, c_in, c_out, ep, s);
+        return launch_conv_big_tile<WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
     if (WD && blocks_one<2, 2, WPH, WD>(n, h, w, c_in, c_out) >= want)
         return launch_one<2, 2, WPH, WD>(in, wt, n, h, w, c_in, c_out, ep, s);
     if (blocks_one<2, 2, WPH>(n, h, w, c_in, c_out) >= want)

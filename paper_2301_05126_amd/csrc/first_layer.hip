@@ -446,7 +446,6 @@ __global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0;
     const int nsteps = (K + 31) / 32;
-#pragma unroll 4
     for (int ks = 0; ks < nsteps; ++ks) {
         const bool ok = ks * 32 + half * 16 < K;         // K % 16 == 0: a 16-byte slice is all in or all out
         const int koff = ok ? ks * 32 : 0;
