@@ -120,7 +120,8 @@ bnn_status bnn_conv_first_int8(const int8_t *in_dev, int n, int h, int w, int c_
  *   in_dev: device, packed uint32 [n][h][w][ceil(c_in/32)].
  *   w_dev:  device, packed uint32 [c_out][3][3][ceil(c_in/32)].
  *   Outputs as for bnn_conv_first_int8 (ho = h, wo = w).
- * Errors: NULL, SHAPE, ALIGN.
+ * Errors: NULL, SHAPE, ALIGN, UNSUPPORTED (c_in > 1024, or one image's packed input of
+ *         2 GiB or more).
  */
 bnn_status bnn_conv_binary(const uint32_t *in_dev, int n, int h, int w, int c_in,
                            const uint32_t *w_dev, int c_out, const bnn_epilogue *ep,

@@ -16,8 +16,9 @@ BNN_DECL_WPH(16)
 
 bool conv_binary_supported(int h, int w, int c_in)
 {
-    (void)h; (void)w;
-    return c_in <= 1024;        // at most 32 words per pixel; the smallest block tile then fits LDS
+    // at most 32 words per pixel (the smallest block tile then fits LDS); one image's packed
+    // input below 2 GiB (32-bit byte offsets inside a block's buffer resource)
+    return c_in <= 1024 && (int64_t)h * w * ((c_in + 31) / 32) * 4 < 0x7fffffffLL;
 }
 
 bnn_status launch_conv_binary(const uint32_t *in, int n, int h, int w, int c_in, const uint32_t *wt,

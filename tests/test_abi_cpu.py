@@ -88,6 +88,7 @@ def test_conv_validation(lib):
     bad_order = lib.Epilogue(P16, None, 2, 5)
     assert f(P16, 1, 8, 8, 32, P16, 32, C.byref(bad_order), None, P16, None) == SHAPE
     assert f(P16, 1, 32, 32, 1 << 16, P16, 32, None, P16, None, None) == UNSUP     # patch > LDS
+    assert f(P16, 1, 1 << 13, 1 << 13, 1024, P16, 32, None, P16, None, None) == UNSUP   # an image of 8 GiB
     g = lib.api._lib.bnn_conv_first_int8
     assert g(None, 1, 8, 8, 1, P16, 32, 3, 3, 1, -1, None, P16, None, None) == NULL
     assert g(P16, 1, 8, 8, 1, P16, 32, 3, 3, 1, 300, None, P16, None, None) == SHAPE
