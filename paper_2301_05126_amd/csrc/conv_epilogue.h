@@ -150,21 +150,24 @@ __device__ __forceinline__ StepWords<TN> load_step_words(const EpiArgs &ep, int 
     return sw;
 }
 
-// quad-lane exchanges (DPP quad_perm [1,0,3,2] and [2,3,0,1])
-__device__ __forceinline__ int quad_xor1(int v) { return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false); }
-__device__ __forceinline__ int quad_xor2(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false); }
-
-// maximum over the four lanes of a quad
-__device__ __forceinline__ int quad_max(int v)
-{
-    v = max(v, quad_xor1(v));
-    return max(v, quad_xor2(v));
-}
-__device__ __forceinline__ float quad_max(float v)
-{
-    v = fmaxf(v, __int_as_float(quad_xor1(__float_as_int(v))));
-    return fmaxf(v, __int_as_float(quad_xor2(__float_as_int(v))));
-}
+// Reductions over the four lanes of a quad, one DPP instruction per exchange (the operation
+// reads its first operand through the quad permute).  Written as inline assembly: the compiler
+// keeps a separate v_mov_dpp per exchange (and, for fmaxf, a canonicalising v_max).  The
+// s_nop covers the two wait states a DPP read needs after a VALU write of the same register.
+#define BNN_QUAD_OP(name, type, cons, insn)                                                                   \
+    __device__ __forceinline__ type name(type v)                                                              \
+    {                                                                                                         \
+        type r;                                                                                               \
+        asm volatile("s_nop 1\n\t" insn " %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf"          \
+                     : "=" cons(r) : cons(v));                                                                \
+        asm volatile("s_nop 1\n\t" insn " %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"          \
+                     : "=" cons(v) : cons(r));                                                                \
+        return v;                                                                                             \
+    }
+BNN_QUAD_OP(quad_max, int, "v", "v_max_i32_dpp")
+BNN_QUAD_OP(quad_max, float, "v", "v_max_f32_dpp")
+BNN_QUAD_OP(quad_or, unsigned, "v", "v_or_b32_dpp")
+#undef BNN_QUAD_OP
 __device__ __forceinline__ unsigned value_bits(int v) { return (unsigned)v; }
 __device__ __forceinline__ unsigned value_bits(float v) { return __float_as_uint(v); }
 
@@ -201,10 +204,7 @@ __device__ __forceinline__ void conv_tile_step_to_lds(GetS gets, int row0, int w
             w = (w ^ sw.nflipw[j]) & sw.okw[j];
             const int row = row0 + i * 32 + l32;
             if (pool == 2) {
-                if (!pool_first) {                   // OR over the window
-                    w |= (unsigned)quad_xor1((int)w);
-                    w |= (unsigned)quad_xor2((int)w);
-                }
+                if (!pool_first) w = quad_or(w);     // OR over the window
                 if (half == 0 && (l32 & 3) == 0) out_lds[(row >> 2) * bw + word0 + j] = w;
             } else {
                 if (half == 0) out_lds[row * bw + word0 + j] = w;
