@@ -45,6 +45,20 @@ template <> struct WordVec<1> { using type = uint32_t; };
 __device__ __forceinline__ uint32_t vec_word(const uint4 &v, int q) { return q == 0 ? v.x : (q == 1 ? v.y : (q == 2 ? v.z : v.w)); }
 __device__ __forceinline__ uint32_t vec_word(const uint2 &v, int q) { return q == 0 ? v.x : v.y; }
 __device__ __forceinline__ uint32_t vec_word(const uint32_t &v, int) { return v; }
+// operand of a word group's first step (see expand_pair_half for the two-word groups)
+template <int V, typename VecT>
+__device__ __forceinline__ v8i expand_first(const VecT &v, uint32_t sgn, uint32_t one)
+{
+    if constexpr (V == 2) {
+        const uint2 lo = expand_pair_half(v, 0, 0, sgn, one), hi = expand_pair_half(v, 0, 1, sgn, one);
+        v8i r;
+        r[0] = (int)lo.x; r[1] = (int)lo.y; r[2] = (int)hi.x; r[3] = (int)hi.y;
+        r[4] = 0; r[5] = 0; r[6] = 0; r[7] = 0;
+        return r;
+    } else {
+        return expand_fp4(vec_word(v, 0), sgn, one);
+    }
+}
 
 __device__ __forceinline__ void vec_set(uint4 &v, int q, uint32_t x) { if (q == 0) v.x = x; else if (q == 1) v.y = x; else if (q == 2) v.z = x; else v.w = x; }
 __device__ __forceinline__ void vec_set(uint2 &v, int q, uint32_t x) { if (q == 0) v.x = x; else v.y = x; }
@@ -375,7 +389,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
             load_a(0, 0, 0);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const v8i e = expand_fp4(vec_word(ra[0][i], 0), sgn, one);
+                const v8i e = expand_first<V>(ra[0][i], sgn, one);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) a[0][i][q] = e[q];
             }
@@ -409,7 +423,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                 load_a(c, 0, 0);
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
-                    const v8i e = expand_fp4(vec_word(ra[0][i], 0), sgn, one);
+                    const v8i e = expand_first<V>(ra[0][i], sgn, one);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) a[0][i][q] = e[q];
                 }
@@ -418,7 +432,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                 load_b(Bc, 0, 0);
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    const v8i e = expand_fp4(vec_word(rb[0][j], 0), sgn, one);
+                    const v8i e = expand_first<V>(rb[0][j], sgn, one);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) b[0][j][q] = e[q];
                 }
@@ -443,7 +457,10 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                 }
                 const bool in_chunk = st + 1 < SPC;
                 const int vg1 = in_chunk ? (st + 1) / V : 0, q1 = in_chunk ? (st + 1) % V : 0;
-                const bool next_a = in_chunk || (XA && more), next_b = in_chunk || (XB && more);
+                // (streamed weights: the chunk index is a run-time value, and the last chunk expands
+                // stale words into operands that the next tile overwrites, rather than branching)
+                const bool next_a = in_chunk || (XA && (WDMA || more)), next_b = in_chunk || (XB && more);
+                uint2 pend[2 * (TM + TN)];                // shifted pairs awaiting their masks
 #pragma unroll
                 for (int k = 0; k < TM * TN; ++k) {
                     const int i = k / TN, j = k % TN;
@@ -451,14 +468,38 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                     // (zero scale operands select the instruction form without block scales)
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                         b[cur_s][j], a[cur_s][i], acc[i][j], 4, 4, 0, 0, 0, 0);
+                    if constexpr (V == 2) {
+                        // Word pairs: TM + TN pairs, two (shift, mask, mask) items each.  An item's
+                        // masks come one MFMA after its shift (no VALU instruction waits for the one
+                        // before it); with a single MFMA per step both fall behind that one.
+                        constexpr int NIT = 2 * (TM + TN), NM = TM * TN, LAG = NM > 1 ? 1 : 0;
 #pragma unroll
-                    for (int d = k * DPM; d < (k + 1) * DPM && d < 4 * (TM + TN); ++d) {
-                        const int wi = d >> 2, part = d & 3;
-                        if (wi < TM) {
-                            if (next_a) a[nxt][wi][part] = (int)expand_part(vec_word(ra[vg1 & 1][wi], q1), part, sgn, one);
-                        } else {
-                            if (next_b)
-                                b[nxt][wi - TM][part] = (int)expand_part(vec_word(rb[vg1 & 1][wi - TM], q1), part, sgn, one);
+                        for (int t2 = 0; t2 < NIT; ++t2) {
+                            const int ks = t2 * (NM - LAG) / NIT;            // MFMA the shift follows
+                            const int wi = t2 >> 1, dp = t2 & 1;
+                            if (!(wi < TM ? next_a : next_b)) continue;
+                            if (ks == k) pend[t2] = shift_pair_half(wi < TM ? ra[vg1 & 1][wi] : rb[vg1 & 1][wi - TM], q1, dp);
+                            if (ks + LAG == k) {
+                                const uint2 e = mask_pair(pend[t2], sgn, one);
+                                if (wi < TM) {
+                                    a[nxt][wi][2 * dp] = (int)e.x;
+                                    a[nxt][wi][2 * dp + 1] = (int)e.y;
+                                } else {
+                                    b[nxt][wi - TM][2 * dp] = (int)e.x;
+                                    b[nxt][wi - TM][2 * dp + 1] = (int)e.y;
+                                }
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int d = k * DPM; d < (k + 1) * DPM && d < 4 * (TM + TN); ++d) {
+                            const int wi = d >> 2, part = d & 3;
+                            if (wi < TM) {
+                                if (next_a) a[nxt][wi][part] = (int)expand_part(vec_word(ra[vg1 & 1][wi], q1), part, sgn, one);
+                            } else {
+                                if (next_b)
+                                    b[nxt][wi - TM][part] = (int)expand_part(vec_word(rb[vg1 & 1][wi - TM], q1), part, sgn, one);
+                            }
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);

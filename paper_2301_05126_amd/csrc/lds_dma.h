@@ -71,6 +71,34 @@ __device__ __forceinline__ uint32_t expand_part(uint32_t w, int part, uint32_t s
     return part == 3 ? ((w & sgn) | one) : (((w << (3 - part)) & sgn) | one);
 }
 
+// The same for two words at once, the words of two consecutive MFMA steps held in a 64-bit
+// register pair: one 64-bit shift moves both (the bits that cross from the low word into the
+// high one land below each nibble's sign position, where the mask drops them), so a pair costs
+// three shifts instead of six.  The two steps split the pair's dwords by shift amount, not by
+// word: step 0 takes the dwords shifted by 3 and 2 of both words, step 1 those shifted by 1 and
+// 0.  Both MFMA operands are built this way, so every bit still meets its partner exactly once
+// over the two steps.  expand_pair_half returns dwords 2*dp and 2*dp+1 of step q's operand.
+// (The shift is written as assembly: the compiler would split it back into 32-bit shifts.)
+__device__ __forceinline__ uint2 shift_pair_half(uint2 w, int q, int dp)
+{
+    const int sh = (q == 0 ? 3 : 1) - dp;
+    if (sh > 0) {
+        const uint64_t p = (uint64_t)w.x | ((uint64_t)w.y << 32);
+        uint64_t r;
+        asm("v_lshlrev_b64 %0, %1, %2" : "=v"(r) : "n"(sh), "v"(p));
+        w = make_uint2((uint32_t)r, (uint32_t)(r >> 32));
+    }
+    return w;
+}
+__device__ __forceinline__ uint2 mask_pair(uint2 w, uint32_t sgn, uint32_t one)
+{
+    return make_uint2((w.x & sgn) | one, (w.y & sgn) | one);
+}
+__device__ __forceinline__ uint2 expand_pair_half(uint2 w, int q, int dp, uint32_t sgn, uint32_t one)
+{
+    return mask_pair(shift_pair_half(w, q, dp), sgn, one);
+}
+
 }  // namespace
 
 }  // namespace bnn
