@@ -171,46 +171,85 @@ BNN_QUAD_OP(quad_or, unsigned, "v", "v_or_b32_dpp")
 __device__ __forceinline__ unsigned value_bits(int v) { return (unsigned)v; }
 __device__ __forceinline__ unsigned value_bits(float v) { return __float_as_uint(v); }
 
+// This lane's 16 result bits of one 32 x 32 accumulator tile, as the bits 8q + 4*half + m of a
+// packed word (register r = 4q + m holds channel 8q + 4*half + m): bit set iff x <= thr.
+// QMAX: the values are first replaced by the maximum over the window's four pixels.
+template <bool QMAX, typename GetR>
+__device__ __forceinline__ unsigned tile_half_word(GetR getr, int half)
+{
+    unsigned code[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int r = 15; r >= 0; --r) {
+        auto v = getr(r);
+        if (QMAX) v = quad_max(v);
+        code[r >> 2] = __builtin_amdgcn_alignbit(code[r >> 2], value_bits(v), 31);
+    }
+    const unsigned w = (((code[3] << 8) | code[2]) << 16) | ((code[1] << 8) | code[0]);
+    return w << (4 * half);
+}
+
+// MODE 0: step; 1: step, then OR over each 2 x 2 window; 2: maximum over the window, then step.
+template <int TM, int TN, int MODE, typename GetS>
+__device__ __forceinline__ void conv_tile_step_mode(GetS gets, int row0, int word0, int bw, int l32, int half,
+                                                    const StepWords<TN> &sw, uint32_t *out_lds)
+{
+    if constexpr (TN % 2 == 0) {
+        // Two channel tiles at a time: lane l and lane l ^ 32 hold complementary nibbles of
+        // both tiles' words; one swap leaves the first tile's word complete in lanes 0..31
+        // and the second tile's in lanes 32..63, and each lane half finishes and stores its own.
+#pragma unroll
+        for (int jp = 0; jp < TN / 2; ++jp) {
+            const unsigned nflip = half ? sw.nflipw[2 * jp + 1] : sw.nflipw[2 * jp];
+            const unsigned ok = half ? sw.okw[2 * jp + 1] : sw.okw[2 * jp];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const unsigned wa = tile_half_word<MODE == 2>([&](int r) { return gets(i, 2 * jp, r); }, half);
+                const unsigned wb = tile_half_word<MODE == 2>([&](int r) { return gets(i, 2 * jp + 1, r); }, half);
+                const auto sw2 = __builtin_amdgcn_permlane32_swap(wa, wb, false, false);
+                unsigned w = ((sw2[0] | sw2[1]) ^ nflip) & ok;
+                const int row = row0 + i * 32 + l32, word = word0 + 2 * jp + half;
+                if (MODE != 0) {
+                    if (MODE == 1) w = quad_or(w);
+                    if ((l32 & 3) == 0) out_lds[(row >> 2) * bw + word] = w;
+                } else {
+                    out_lds[row * bw + word] = w;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                unsigned w = tile_half_word<MODE == 2>([&](int r) { return gets(i, j, r); }, half);
+                // merge the two lane halves (lane l and lane l ^ 32 hold complementary nibbles)
+                const auto sw2 = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+                w = ((sw2[0] | sw2[1]) ^ sw.nflipw[j]) & sw.okw[j];
+                const int row = row0 + i * 32 + l32;
+                if (MODE != 0) {
+                    if (MODE == 1) w = quad_or(w);
+                    if (half == 0 && (l32 & 3) == 0) out_lds[(row >> 2) * bw + word0 + j] = w;
+                } else {
+                    if (half == 0) out_lds[row * bw + word0 + j] = w;
+                }
+            }
+        }
+    }
+}
+
 // Step (+ pool) of one wave's tiles into the block's LDS output tile.
 // gets(i, j, r): finished biased sum (int or float) of pixel tile i, channel tile j, register
 // r; its sign bit is set iff x <= thr.  out_lds is [output pixel of the block][bw words]; an
 // output pixel is a GEMM row (pool 1) or a window (pool 2).  word0 = index, inside the
-// block's bw words, of this wave's first 32 channels.
+// block's bw words, of this wave's first 32 channels.  (One straight-line variant per mode.)
 template <int TM, int TN, typename GetS>
 __device__ __forceinline__ void conv_tile_step_to_lds(GetS gets, int row0, int word0, int bw, int l32, int half,
                                                       const StepWords<TN> &sw, int pool, bool pool_first,
                                                       uint32_t *out_lds)
 {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            // code[q] bit m = (x_r <= thr_r) for register r = 4q + m: channels 8q + 4*half + m
-            unsigned code[4] = {0u, 0u, 0u, 0u};
-            if (pool == 2 && pool_first) {           // max over the window's four pixels first
-#pragma unroll
-                for (int r = 15; r >= 0; --r)
-                    code[r >> 2] = __builtin_amdgcn_alignbit(code[r >> 2], value_bits(quad_max(gets(i, j, r))), 31);
-            } else {
-#pragma unroll
-                for (int r = 15; r >= 0; --r)
-                    code[r >> 2] = __builtin_amdgcn_alignbit(code[r >> 2], value_bits(gets(i, j, r)), 31);
-            }
-            unsigned w = (((code[3] << 8) | code[2]) << 16) | ((code[1] << 8) | code[0]);
-            w <<= 4 * half;
-            // merge the two lane halves (lane l and lane l ^ 32 hold complementary nibbles)
-            const auto sw2 = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-            w = sw2[0] | sw2[1];
-            w = (w ^ sw.nflipw[j]) & sw.okw[j];
-            const int row = row0 + i * 32 + l32;
-            if (pool == 2) {
-                if (!pool_first) w = quad_or(w);     // OR over the window
-                if (half == 0 && (l32 & 3) == 0) out_lds[(row >> 2) * bw + word0 + j] = w;
-            } else {
-                if (half == 0) out_lds[row * bw + word0 + j] = w;
-            }
-        }
-    }
+    if (pool == 2 && pool_first) conv_tile_step_mode<TM, TN, 2>(gets, row0, word0, bw, l32, half, sw, out_lds);
+    else if (pool == 2) conv_tile_step_mode<TM, TN, 1>(gets, row0, word0, bw, l32, half, sw, out_lds);
+    else conv_tile_step_mode<TM, TN, 0>(gets, row0, word0, bw, l32, half, sw, out_lds);
 }
 
 // Copy the block's LDS output tile to the packed activation tensor: one thread per output
