@@ -172,12 +172,19 @@ __device__ __forceinline__ int div_magic(int n, unsigned mg) { return mg ? (int)
 // patch buffer afterwards, so their latency hides behind the tile and the block needs one
 // barrier per tile.  Otherwise the patch is staged in place between two barriers.  Packed
 // words go to one of two LDS output tiles and are copied out after the next barrier.
-template <int NG, bool PIPE>
+//
+// NS > 0 (the launcher's choice for PIPE when a kernel row fits 16 bytes): the number of
+// 32-wide K steps is the compile-time NS and a K step's two 16-byte halves are two kernel
+// rows, so every LDS address of the tile loop is a per-lane base fixed at kernel start plus an
+// immediate, and the pixel-tile and channel-group loops are straight-line code.
+template <int NG, bool PIPE, int NS>
 __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restrict__ in,
                                                        const int8_t *__restrict__ wt, FirstGeomM g, EpiArgs ep)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int ws = g.kp + 16;                                   // weight row stride in bytes
+    constexpr bool FAST = NS > 0;
+    constexpr int NSA = FAST ? NS : 1;
+    const int ws = FAST ? NS * 32 + 16 : g.kp + 16;             // weight row stride in bytes
     constexpr int TN = 2;                                       // 32-channel tiles per group
     constexpr int BW = 2 * NG;                                  // packed output words per pixel
     unsigned char *Wl = smem;                                   // [64*NG][ws]
@@ -239,7 +246,23 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
         pixbyte[i] = ((il * ph + py) * pw + px) * g.c_in;
     }
     const int u16 = g.slp >> 4;                  // 16-byte units per kernel row
-    const int nsteps = g.kp >> 5;
+    const int nsteps = FAST ? NS : g.kp >> 5;
+    // FAST: dword index and byte shift of this lane's 16 operand bytes per (pixel tile, K step);
+    // kernel rows past the last one read the patch start and meet zero weights
+    int gd[2][NSA];
+    unsigned gsh[2][NSA];
+    if (FAST) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int ks = 0; ks < NSA; ++ks) {
+                const int ti = 2 * ks + half;
+                const int addr = ti < g.kh ? pixbyte[i] + ti * pw * g.c_in : 0;
+                gd[i][ks] = addr >> 2;
+                gsh[i][ks] = (unsigned)addr & 3u;
+            }
+    }
+    const unsigned char *wlane = Wl + l32 * ws + half * 16;     // this lane's bytes of a weight row tile
 
     // per-channel step parameters, fetched once per block (the first barrier of the tile
     // loop publishes the accumulator start values; sums stay far below 2^30)
@@ -360,29 +383,36 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
 
         // one 32-pixel tile after the other (keeps the register footprint small enough for
         // three blocks per compute unit)
-#pragma unroll 1
+        constexpr int IU = FAST ? 2 : 1, GU = FAST ? NG : 1;
+#pragma unroll IU
         for (int i = 0; i < 2; ++i) {
-            // activation operands of all K steps (at most 4), gathered once per pixel tile
-            const int pixb = i ? pixbyte[1] : pixbyte[0];
+            // activation operands of all K steps (at most 4), gathered once per pixel tile:
+            // 16 bytes from an arbitrary byte address = five aligned dwords, funnel-shifted
             v4i a[4];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                if (ks >= nsteps) break;
-                const int k16 = 2 * ks + half;
-                const int ti = k16 / u16, off = (k16 - ti * u16) << 4;
-                // 16 bytes from an arbitrary byte address: five aligned dwords, funnel-shifted
-                const int addr = ti < g.kh ? pixb + ti * pw * g.c_in + off : 0;
-                const int d = addr >> 2;
-                const unsigned sh = (unsigned)addr & 3u;
+            auto gather16 = [&](int ks, int d, unsigned sh) {
                 const unsigned w0 = P32[d], w1 = P32[d + 1], w2 = P32[d + 2], w3 = P32[d + 3], w4 = P32[d + 4];
                 a[ks][0] = (int)__builtin_amdgcn_alignbyte(w1, w0, sh);
                 a[ks][1] = (int)__builtin_amdgcn_alignbyte(w2, w1, sh);
                 a[ks][2] = (int)__builtin_amdgcn_alignbyte(w3, w2, sh);
                 a[ks][3] = (int)__builtin_amdgcn_alignbyte(w4, w3, sh);
+            };
+            if constexpr (FAST) {
+#pragma unroll
+                for (int ks = 0; ks < NS; ++ks) gather16(ks, gd[i][ks], gsh[i][ks]);
+            } else {
+                const int pixb = i ? pixbyte[1] : pixbyte[0];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    if (ks >= nsteps) break;
+                    const int k16 = 2 * ks + half;
+                    const int ti = k16 / u16, off = (k16 - ti * u16) << 4;
+                    const int addr = ti < g.kh ? pixb + ti * pw * g.c_in + off : 0;
+                    gather16(ks, addr >> 2, (unsigned)addr & 3u);
+                }
             }
             const int row0 = wave * 64 + i * 32;
 
-#pragma unroll 1
+#pragma unroll GU
             for (int grp = 0; grp < NG; ++grp) {
                 __builtin_amdgcn_s_setprio(1);           // multiplies outrank other waves' epilogues
                 // accumulators start at the channels' biases (see stage_bias_i32)
@@ -392,10 +422,10 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
                 for (int j = 0; j < TN; ++j) acc[j] = load_bias16<v16i>(Tg + j * 32, half);
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
-                    if (ks >= nsteps) break;
+                    if (FAST ? ks >= NS : ks >= nsteps) break;
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
-                        const v4i b = *reinterpret_cast<const v4i *>(Wl + ((grp * TN + j) * 32 + l32) * ws + ks * 32 + half * 16);
+                        const v4i b = *reinterpret_cast<const v4i *>(wlane + (grp * TN + j) * 32 * ws + ks * 32);
                         acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a[ks], acc[j], 0, 0, 0);   // rows = channels
                     }
                 }
@@ -417,6 +447,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
                     conv_tile_step_to_lds<1, TN>(gets, row0, grp * TN, BW, l32, half, cursw, ep.pool,
                                                  ep.pool_first != 0, Oc);
                 }
+                if (FAST) __builtin_amdgcn_sched_barrier(0);      // one group's registers at a time
             }
         }
         if (PIPE && next_item < g.n_items) store_bytes(Pl + ((it + 1) & 1) * g.patch_bytes, 0, vn);
@@ -491,10 +522,16 @@ bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, 
     // persistent blocks: weights are staged once, then the block walks its share of the tiles
     const int64_t cap = 256 * 3;
     const unsigned bx = (unsigned)(items < cap ? items : cap);
-    if (pipe)
-        hipLaunchKernelGGL((conv_first_mfma<NG, true>), dim3(bx, (unsigned)g.n_co_tiles), dim3(256), smem, s, in, wt, g, ep);
+    const dim3 grid(bx, (unsigned)g.n_co_tiles);
+    const int ns = g.kp >> 5;
+    if (pipe && g.slp == 16 && ns == 1)
+        hipLaunchKernelGGL((conv_first_mfma<NG, true, 1>), grid, dim3(256), smem, s, in, wt, g, ep);
+    else if (pipe && g.slp == 16 && ns == 2)
+        hipLaunchKernelGGL((conv_first_mfma<NG, true, 2>), grid, dim3(256), smem, s, in, wt, g, ep);
+    else if (pipe)
+        hipLaunchKernelGGL((conv_first_mfma<NG, true, 0>), grid, dim3(256), smem, s, in, wt, g, ep);
     else
-        hipLaunchKernelGGL((conv_first_mfma<NG, false>), dim3(bx, (unsigned)g.n_co_tiles), dim3(256), smem, s, in, wt, g, ep);
+        hipLaunchKernelGGL((conv_first_mfma<NG, false, 0>), grid, dim3(256), smem, s, in, wt, g, ep);
     return hip_result(hipGetLastError());
 }
 
