@@ -171,21 +171,32 @@ BNN_QUAD_OP(quad_or, unsigned, "v", "v_or_b32_dpp")
 __device__ __forceinline__ unsigned value_bits(int v) { return (unsigned)v; }
 __device__ __forceinline__ unsigned value_bits(float v) { return __float_as_uint(v); }
 
-// This lane's 16 result bits of one 32 x 32 accumulator tile, as the bits 8q + 4*half + m of a
-// packed word (register r = 4q + m holds channel 8q + 4*half + m): bit set iff x <= thr.
+// This lane's 16 result bits of one 32 x 32 accumulator tile (register r = 4q + m holds channel
+// 8q + 4*half + m; bit set iff x <= thr): one funnel shift per value appends the sign bits to a
+// 16-bit chain, ordered so that chain | chain << 12 has nibble q of the result in the low
+// nibble of byte q; the other nibbles hold leftovers that merge_half_words drops.
 // QMAX: the values are first replaced by the maximum over the window's four pixels.
 template <bool QMAX, typename GetR>
-__device__ __forceinline__ unsigned tile_half_word(GetR getr, int half)
+__device__ __forceinline__ unsigned tile_half_word(GetR getr)
 {
-    unsigned code[4] = {0u, 0u, 0u, 0u};
+    unsigned chain = 0u;
 #pragma unroll
-    for (int r = 15; r >= 0; --r) {
-        auto v = getr(r);
-        if (QMAX) v = quad_max(v);
-        code[r >> 2] = __builtin_amdgcn_alignbit(code[r >> 2], value_bits(v), 31);
+    for (int q : {3, 1, 2, 0}) {                  // chain nibbles 3, 2, 1, 0 = result nibbles 3, 1, 2, 0
+#pragma unroll
+        for (int m = 3; m >= 0; --m) {
+            auto v = getr(4 * q + m);
+            if (QMAX) v = quad_max(v);
+            chain = __builtin_amdgcn_alignbit(chain, value_bits(v), 31);
+        }
     }
-    const unsigned w = (((code[3] << 8) | code[2]) << 16) | ((code[1] << 8) | code[0]);
-    return w << (4 * half);
+    return (chain << 12) | chain;
+}
+
+// lo / hi: tile_half_word of the lanes with half == 0 / half == 1 for the same 32 channels and
+// pixel -> the 32 result bits (low nibble of every byte from lo, high nibble from hi).
+__device__ __forceinline__ unsigned merge_half_words(unsigned lo, unsigned hi)
+{
+    return (lo & 0x0f0f0f0fu) | ((hi << 4) & 0xf0f0f0f0u);
 }
 
 // MODE 0: step; 1: step, then OR over each 2 x 2 window; 2: maximum over the window, then step.
@@ -193,6 +204,12 @@ template <int TM, int TN, int MODE, typename GetS>
 __device__ __forceinline__ void conv_tile_step_mode(GetS gets, int row0, int word0, int bw, int l32, int half,
                                                     const StepWords<TN> &sw, uint32_t *out_lds)
 {
+    // LDS word index of pixel tile 0, channel tile 0 (row0 is a multiple of 32); kept in a
+    // register as it is (the compiler would rebuild it from its parts before every store)
+    unsigned idx0 = (MODE != 0 ? (unsigned)(row0 + l32) >> 2 : (unsigned)(row0 + l32)) * bw + word0;
+    if (TN % 2 == 0) idx0 += half;
+    asm volatile("" : "+v"(idx0));
+    constexpr int ISTRIDE = MODE != 0 ? 8 : 32;              // output pixels per pixel tile
     if constexpr (TN % 2 == 0) {
         // Two channel tiles at a time: lane l and lane l ^ 32 hold complementary nibbles of
         // both tiles' words; one swap leaves the first tile's word complete in lanes 0..31
@@ -203,17 +220,13 @@ __device__ __forceinline__ void conv_tile_step_mode(GetS gets, int row0, int wor
             const unsigned ok = half ? sw.okw[2 * jp + 1] : sw.okw[2 * jp];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const unsigned wa = tile_half_word<MODE == 2>([&](int r) { return gets(i, 2 * jp, r); }, half);
-                const unsigned wb = tile_half_word<MODE == 2>([&](int r) { return gets(i, 2 * jp + 1, r); }, half);
+                const unsigned wa = tile_half_word<MODE == 2>([&](int r) { return gets(i, 2 * jp, r); });
+                const unsigned wb = tile_half_word<MODE == 2>([&](int r) { return gets(i, 2 * jp + 1, r); });
+                // after the swap: [0] = what the half-0 lanes computed, [1] = the half-1 lanes
                 const auto sw2 = __builtin_amdgcn_permlane32_swap(wa, wb, false, false);
-                unsigned w = ((sw2[0] | sw2[1]) ^ nflip) & ok;
-                const int row = row0 + i * 32 + l32, word = word0 + 2 * jp + half;
-                if (MODE != 0) {
-                    if (MODE == 1) w = quad_or(w);
-                    if ((l32 & 3) == 0) out_lds[(row >> 2) * bw + word] = w;
-                } else {
-                    out_lds[row * bw + word] = w;
-                }
+                unsigned w = (merge_half_words(sw2[0], sw2[1]) ^ nflip) & ok;
+                if (MODE == 1) w = quad_or(w);
+                if (MODE == 0 || (l32 & 3) == 0) out_lds[idx0 + i * ISTRIDE * bw + 2 * jp] = w;
             }
         }
     } else {
@@ -221,17 +234,12 @@ __device__ __forceinline__ void conv_tile_step_mode(GetS gets, int row0, int wor
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                unsigned w = tile_half_word<MODE == 2>([&](int r) { return gets(i, j, r); }, half);
+                unsigned w = tile_half_word<MODE == 2>([&](int r) { return gets(i, j, r); });
                 // merge the two lane halves (lane l and lane l ^ 32 hold complementary nibbles)
                 const auto sw2 = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-                w = ((sw2[0] | sw2[1]) ^ sw.nflipw[j]) & sw.okw[j];
-                const int row = row0 + i * 32 + l32;
-                if (MODE != 0) {
-                    if (MODE == 1) w = quad_or(w);
-                    if (half == 0 && (l32 & 3) == 0) out_lds[(row >> 2) * bw + word0 + j] = w;
-                } else {
-                    if (half == 0) out_lds[row * bw + word0 + j] = w;
-                }
+                w = (merge_half_words(sw2[0], sw2[1]) ^ sw.nflipw[j]) & sw.okw[j];
+                if (MODE == 1) w = quad_or(w);
+                if (half == 0 && (MODE == 0 || (l32 & 3) == 0)) out_lds[idx0 + i * ISTRIDE * bw + j] = w;
             }
         }
     }
