@@ -324,6 +324,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         return pos;
     };
 
+    const CopyLane copy_lane = make_copy_lane(64 * TM, tile_pos(next), ep.pool, t);
     if (slot < g.n_ptiles) fetch_patch(next, 0);
     if (WDMA && slot < g.n_ptiles) dma_w(0, 0);
     int cc = 0;                                            // chunks done so far (WDMA buffer parity)
@@ -344,7 +345,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         __syncthreads();                                      // ... for every wave; previous tile fully consumed
         if (g.dbuf && ptile + g.slots < g.n_ptiles) fetch_patch(next, buf ^ 1);
         if (ep.packed && it > 0)
-            conv_tile_copy_out<BW>(Os + ((it - 1) & 1) * (64 * TM * BW), 64 * TM, o_blk >> 5, tile_pos(prev), ep, t);
+            conv_tile_copy_out<BW>(Os + ((it - 1) & 1) * (64 * TM * BW), copy_lane, o_blk >> 5, tile_pos(prev), ep);
 
         __builtin_amdgcn_s_setprio(1);                        // the multiply phase outranks another wave's epilogue
         // accumulators start at the channels' biases (see stage_bias_f32)
@@ -529,7 +530,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     }
     if (ep.packed && it > 0) {
         __syncthreads();
-        conv_tile_copy_out<BW>(Os + ((it - 1) & 1) * (64 * TM * BW), 64 * TM, o_blk >> 5, tile_pos(cur), ep, t);
+        conv_tile_copy_out<BW>(Os + ((it - 1) & 1) * (64 * TM * BW), copy_lane, o_blk >> 5, tile_pos(cur), ep);
     }
 }
 

@@ -52,6 +52,9 @@ __device__ __forceinline__ void conv_tile_store_preact(GetX getx, int row0, int 
                                                        const TilePos &p, int32_t *preact)
 {
     const bool vec_ok = (p.c_out & 3) == 0;
+    // (the address arithmetic below hangs on a value the compiler cannot see through, so that it
+    // stays inside the caller's "raw output requested" branch instead of running for every tile)
+    asm volatile("" : "+v"(l32));
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         int img, y, x;
@@ -260,52 +263,70 @@ __device__ __forceinline__ void conv_tile_step_to_lds(GetS gets, int row0, int w
     else conv_tile_step_mode<TM, TN, 0>(gets, row0, word0, bw, l32, half, sw, out_lds);
 }
 
-// Copy the block's LDS output tile to the packed activation tensor: one thread per output
-// pixel in raster order of the tile, bw consecutive words each (vector stores when the
-// tensor's words-per-pixel is a multiple of bw).  All threads of the block call it, after a
-// barrier that follows conv_tile_step_to_lds.  blk_word0 = first word index of the block.
-template <int BW>
-__device__ __forceinline__ void conv_tile_copy_out(const uint32_t *out_lds, int block_rows, int blk_word0,
-                                                   const TilePos &p, const EpiArgs &ep, int t)
+// Copy of the block's LDS output tile to the packed activation tensor: thread t moves output
+// pixel t of the tile (raster order; block_rows <= 256 pixels, bw consecutive words each, as
+// vector stores when the tensor's words-per-pixel is a multiple of bw).  What does not depend
+// on the tile's position is worked out once per kernel (make_copy_lane); all threads of the
+// block call conv_tile_copy_out after a barrier that follows conv_tile_step_to_lds.
+struct CopyLane {
+    int tx, ty, il;     // output pixel relative to the tile origin: column, row, image
+    int src;            // its index in the LDS tile
+    int rel;            // its word offset from the tile origin's pixel in the output tensor
+    bool active;        // the tile has such a pixel
+};
+
+// p: any tile position of this kernel (only the geometry is used).
+__device__ __forceinline__ CopyLane make_copy_lane(int block_rows, const TilePos &p, int pool, int t)
 {
-    const int pool = ep.pool;
     const int cwo = (p.c_out + 31) >> 5;
     const int lw = pool == 2 ? p.ltw - 1 : p.ltw, lh = pool == 2 ? p.lth - 1 : p.lth;
     const int oh = pool == 2 ? p.h >> 1 : p.h, ow = pool == 2 ? p.w >> 1 : p.w;
-    const int oy0 = pool == 2 ? p.y0 >> 1 : p.y0, ox0 = pool == 2 ? p.x0 >> 1 : p.x0;
     const int n_out = pool == 2 ? block_rows >> 2 : block_rows;
+    CopyLane c;
+    c.active = t < n_out;
+    c.tx = t & ((1 << lw) - 1);
+    c.ty = (t >> lw) & ((1 << lh) - 1);
+    c.il = t >> (lw + lh);
+    // LDS index: windows are stored x-fastest; un-pooled pixels are window-major
+    if (pool == 2) {
+        c.src = t;
+    } else {
+        const int wq = (c.il << (lw + lh - 2)) | ((c.ty >> 1) << (lw - 1)) | (c.tx >> 1);
+        c.src = wq * 4 + (c.ty & 1) * 2 + (c.tx & 1);
+    }
+    // several images per tile only when an image is smaller than the tile: the offset is small
+    c.rel = ((c.il * oh + c.ty) * ow + c.tx) * cwo;
+    return c;
+}
+
+// blk_word0 = first word index of the block inside a pixel's words.
+template <int BW>
+__device__ __forceinline__ void conv_tile_copy_out(const uint32_t *out_lds, const CopyLane &c, int blk_word0,
+                                                   const TilePos &p, const EpiArgs &ep)
+{
+    const int pool = ep.pool;
+    const int cwo = (p.c_out + 31) >> 5;
+    const int oh = pool == 2 ? p.h >> 1 : p.h, ow = pool == 2 ? p.w >> 1 : p.w;
+    const int oy0 = pool == 2 ? p.y0 >> 1 : p.y0, ox0 = pool == 2 ? p.x0 >> 1 : p.x0;
     const bool vec_ok = (cwo % BW) == 0;
-    for (int q = t; q < n_out; q += 256) {
-        const int tx = q & ((1 << lw) - 1);
-        const int ty = (q >> lw) & ((1 << lh) - 1);
-        const int il = q >> (lw + lh);
-        // LDS index: windows are stored x-fastest; un-pooled pixels are window-major
-        int src;
-        if (pool == 2) {
-            src = q;
-        } else {
-            const int wq = (il << (lw + lh - 2)) | ((ty >> 1) << (lw - 1)) | (tx >> 1);
-            src = wq * 4 + (ty & 1) * 2 + (tx & 1);
-        }
-        const int img = p.img0 + il, y = oy0 + ty, x = ox0 + tx;
-        if (img < p.n && y < oh && x < ow) {
-            uint32_t *dst = ep.packed + (((int64_t)img * oh + y) * ow + x) * cwo + blk_word0;
-            const uint32_t *sp = out_lds + src * BW;
-            if (vec_ok) {
-                if (BW == 8) {
-                    reinterpret_cast<uint4 *>(dst)[0] = reinterpret_cast<const uint4 *>(sp)[0];
-                    reinterpret_cast<uint4 *>(dst)[1] = reinterpret_cast<const uint4 *>(sp)[1];
-                } else if (BW == 4) *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(sp);
-                else if (BW == 2) *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(sp);
-                else {
+    if (c.active && p.img0 + c.il < p.n && oy0 + c.ty < oh && ox0 + c.tx < ow) {
+        // the origin's part of the address is the same for every thread
+        uint32_t *dst = ep.packed + ((((int64_t)p.img0 * oh + oy0) * ow + ox0) * cwo + blk_word0) + c.rel;
+        const uint32_t *sp = out_lds + c.src * BW;
+        if (vec_ok) {
+            if (BW == 8) {
+                reinterpret_cast<uint4 *>(dst)[0] = reinterpret_cast<const uint4 *>(sp)[0];
+                reinterpret_cast<uint4 *>(dst)[1] = reinterpret_cast<const uint4 *>(sp)[1];
+            } else if (BW == 4) *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(sp);
+            else if (BW == 2) *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(sp);
+            else {
 #pragma unroll
-                    for (int k = 0; k < BW; ++k) dst[k] = sp[k];
-                }
-            } else {
-#pragma unroll
-                for (int k = 0; k < BW; ++k)
-                    if (blk_word0 + k < cwo) dst[k] = sp[k];
+                for (int k = 0; k < BW; ++k) dst[k] = sp[k];
             }
+        } else {
+#pragma unroll
+            for (int k = 0; k < BW; ++k)
+                if (blk_word0 + k < cwo) dst[k] = sp[k];
         }
     }
 }

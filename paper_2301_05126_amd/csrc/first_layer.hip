@@ -353,6 +353,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
 
     int vn[4];
     Item cur = decode(blockIdx.x < (unsigned)g.n_items ? (int)blockIdx.x : 0), prev = cur, nxt = cur;
+    const CopyLane copy_lane = make_copy_lane(256, item_pos(cur), ep.pool, t);
     if (PIPE && (int)blockIdx.x < g.n_items) {
         load_bytes_pipe(cur, vn);
         store_bytes(Pl, 0, vn);
@@ -376,7 +377,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
         __syncthreads();          // patch (and, the first time, weights and start values) visible
         if (PIPE && next_item < g.n_items) load_bytes_pipe(nxt, vn);
         if (ep.packed && it > 0)
-            conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), 256, o_blk >> 5, item_pos(prev), ep, t);
+            conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), copy_lane, o_blk >> 5, item_pos(prev), ep);
         const unsigned *P32 = reinterpret_cast<const unsigned *>(Pc);
 
         const TilePos pos = item_pos(cur);
@@ -454,7 +455,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restri
     }
     if (ep.packed && it > 0) {
         __syncthreads();
-        conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), 256, o_blk >> 5, item_pos(cur), ep, t);
+        conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), copy_lane, o_blk >> 5, item_pos(cur), ep);
     }
 }
 
