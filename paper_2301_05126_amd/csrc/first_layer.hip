@@ -178,7 +178,7 @@ __device__ __forceinline__ int div_magic(int n, unsigned mg) { return mg ? (int)
 // rows, so every LDS address of the tile loop is a per-lane base fixed at kernel start plus an
 // immediate, and the pixel-tile and channel-group loops are straight-line code.
 template <int NG, bool PIPE, int NS>
-__global__ __launch_bounds__(256, 3) void conv_first_mfma(const int8_t *__restrict__ in,
+__global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int8_t *__restrict__ in,
                                                        const int8_t *__restrict__ wt, FirstGeomM g, EpiArgs ep)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -521,13 +521,14 @@ bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, 
     if (smem > 64 * 1024 || items > 0x7fffffffLL || g.n_co_tiles > 65535) return BNN_ERR_UNSUPPORTED;
     g.n_items = (int)items;
     // persistent blocks: weights are staged once, then the block walks its share of the tiles
-    const int64_t cap = 256 * 3;
+    const int ns = g.kp >> 5;
+    const bool fast = pipe && g.slp == 16 && ns <= 2;           // the straight-line variants: four blocks per CU
+    const int64_t cap = 256 * (fast ? 4 : 3);
     const unsigned bx = (unsigned)(items < cap ? items : cap);
     const dim3 grid(bx, (unsigned)g.n_co_tiles);
-    const int ns = g.kp >> 5;
-    if (pipe && g.slp == 16 && ns == 1)
+    if (fast && ns == 1)
         hipLaunchKernelGGL((conv_first_mfma<NG, true, 1>), grid, dim3(256), smem, s, in, wt, g, ep);
-    else if (pipe && g.slp == 16 && ns == 2)
+    else if (fast)
         hipLaunchKernelGGL((conv_first_mfma<NG, true, 2>), grid, dim3(256), smem, s, in, wt, g, ep);
     else if (pipe)
         hipLaunchKernelGGL((conv_first_mfma<NG, true, 0>), grid, dim3(256), smem, s, in, wt, g, ep);
