@@ -201,7 +201,11 @@ def test_conv_binary_closed_form_borders():
 FIRST_SHAPES = [(2, 28, 28, 1, 64, 3, 3, 1, -1, 2), (2, 32, 32, 3, 128, 3, 3, 1, -1, 1),
                 (64, 1, 1, 784, 512, 1, 1, 0, -1, 1), (3, 8, 8, 3, 32, 3, 3, 1, 0, 2),
                 (1, 5, 7, 2, 40, 3, 3, 1, 7, 1), (2, 6, 6, 3, 33, 5, 3, 2, -1, 2),
-                (1, 4, 4, 4, 8, 1, 1, 0, -1, 1), (300, 2, 2, 5, 70, 3, 3, 1, -1, 2)]
+                (1, 4, 4, 4, 8, 1, 1, 0, -1, 1), (300, 2, 2, 5, 70, 3, 3, 1, -1, 2),
+                # one K step (two kernel rows), two channel groups; four full kernel rows with a ragged
+                # second channel tile; kernel rows wider than 16 bytes with a patch beyond 1 KB
+                (2, 9, 9, 2, 96, 2, 2, 0, -1, 1), (1, 16, 16, 4, 130, 4, 4, 1, -1, 1),
+                (2, 12, 12, 8, 64, 3, 3, 1, 3, 2)]
 
 
 @pytest.mark.parametrize("n,h,w,ci,co,kh,kw,pad,padv,pool", FIRST_SHAPES)
