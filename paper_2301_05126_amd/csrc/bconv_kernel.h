@@ -360,9 +360,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
         // Raw words of a V-step group (TM pixels' words, TN channels' words) and the expanded
         // operands of the current and the next MFMA step.  The pipeline "read words, expand
         // them, multiply" runs across chunk borders where the data allows it (XA: pixel words
-        // always, the patch is resident; XB: channel words when the weights are resident or arrive
-        // by DMA, whose chunks are published one word group before the previous chunk ends).
-        constexpr bool XA = RES || WDMA, XB = RES || WDMA;
+        // always, the patch is resident; XB: channel words only when the weights are resident).
+        constexpr bool XA = RES || WDMA, XB = RES;
         vec_t ra[2][TM], rb[2][TN];
         v8i a[2][TM], b[2][TN];
 #pragma unroll
@@ -403,10 +402,12 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
 #pragma unroll CUNROLL
         for (int c = 0; c < NCHUNK; ++c) {
             if (WDMA) {
-                // Chunk 0 was published by the tile's opening barrier and chunk 1 is requested
-                // here; every later chunk c + 1 is published, and chunk c + 2 requested, before
-                // the last word group of chunk c (see the step loop).
-                if (c == 0 && NCHUNK > 1) dma_w(1, (cc + 1) & 1);
+                if (c > 0) {
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this chunk has landed
+                    __syncthreads();              // ... for every wave; previous chunk consumed
+                }
+                // next chunk of the cyclic sequence into the other buffer
+                if (c + 1 < NCHUNK || ptile + g.slots < g.n_ptiles) dma_w(c + 1 < NCHUNK ? c + 1 : 0, (cc + 1) & 1);
             } else if (!RES) {
                 if (c > 0) __syncthreads();       // previous chunk consumed
                 store_w(0);
@@ -414,9 +415,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                 if (c + 1 < NCHUNK) load_w(c + 1);
             }
             const uint32_t *Bc = RES ? Bs + c * BN * LSB : (WDMA ? Bs + (cc & 1) * BN * LSB : Bs);
-            // next chunk's weights: the following resident chunk / the other DMA buffer
-            const uint32_t *Bn = WDMA ? Bs + ((cc + 1) & 1) * BN * LSB : Bc + BN * LSB;
-            const int cbuf = cc & 1;
+            const uint32_t *Bn = Bc + BN * LSB;            // next chunk's weights (resident weights only)
             if (WDMA) ++cc;
             const bool more = c + 1 < NCHUNK;
 
@@ -452,14 +451,6 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                         load_a(c, vg + 1, (vg + 1) & 1);
                         load_b(Bc, vg + 1, (vg + 1) & 1);
                     } else if (more) {                    // first group of the next chunk
-                        if (WDMA) {
-                            // Every read of this chunk has been issued and awaited by now (the last
-                            // group was read two steps ago): after the barrier the next chunk is
-                            // visible to all waves and this chunk's buffer may take the chunk after it.
-                            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                            __syncthreads();
-                            if (c + 2 < NCHUNK || ptile + g.slots < g.n_ptiles) dma_w(c + 2 < NCHUNK ? c + 2 : 0, cbuf);
-                        }
                         if (XA) load_a(c + 1, 0, 0);
                         if (XB) load_b(Bn, 0, 0);
                     }
@@ -469,7 +460,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                 const int vg1 = in_chunk ? (st + 1) / V : 0, q1 = in_chunk ? (st + 1) % V : 0;
                 // (streamed weights: the chunk index is a run-time value, and the last chunk expands
                 // stale words into operands that the next tile overwrites, rather than branching)
-                const bool next_a = in_chunk || (XA && (WDMA || more)), next_b = in_chunk || (XB && (WDMA || more));
+                const bool next_a = in_chunk || (XA && (WDMA || more)), next_b = in_chunk || (XB && more);
                 uint2 pend[2 * (TM + TN)];                // shifted pairs awaiting their masks
 #pragma unroll
                 for (int k = 0; k < TM * TN; ++k) {
