@@ -154,18 +154,17 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     const int pw = tw + 2, ph = th + 2;
     const int tiles_per_group = g.tiles_x * g.tiles_y;
 
-    // ---- per-channel step parameters and (if resident) all weight chunks: once per block
+    // ---- per-channel step parameters and (if resident) all weight chunks: once per block,
+    // requested further down, behind the first patch, so that all of it is in flight together
     const int corr = 9 * CWP * 32 - g.k_bits;          // padded positions all counted as +1
     StepWords<TN> sw;
-    if (ep.packed) sw = load_step_words<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
-    stage_bias_f32(ep, o_blk, BN, g.c_out, g.k_bits + 1, corr, Ts, t);
     const float *Tw = Ts + wn * TN * 32;               // this wave's channels
 
     // weight staging: LDS row = [half 0: SPC words][half 1: SPC words]; the word of
     // (half, step) is W[o][tap][half*WPH + cwi] with tap = step / WPH, cwi = step % WPH.
     vec_t pb[STG];
     const bool wvec_ok = (g.cw % V) == 0;
-    auto load_w = [&](int chunk) {
+    auto load_w_to = [&](int chunk, vec_t (&dst)[STG]) {
         // Branch-free inside each loop, so that all loads of a chunk are in flight together:
         // rows or words that do not exist read the first weight word and are zeroed afterwards.
         auto unit = [&](int r, bool &row_ok, int &cwpos) {
@@ -189,7 +188,7 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                 vec_t v = *reinterpret_cast<const vec_t *>(ok ? src : wt);
 #pragma unroll
                 for (int q = 0; q < V; ++q) vec_set(v, q, ok ? vec_word(v, q) : 0u);
-                pb[r] = v;
+                dst[r] = v;
             }
         } else {
 #pragma unroll
@@ -204,25 +203,20 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
                     const uint32_t x = *(ok ? src + q : wt);
                     vec_set(v, q, ok ? x : 0u);
                 }
-                pb[r] = v;
+                dst[r] = v;
             }
         }
     };
-    auto store_w = [&](int buf) {
+    auto store_w_from = [&](int buf, const vec_t (&src)[STG]) {
 #pragma unroll
         for (int r = 0; r < STG; ++r) {
             const int idx = t + 256 * r;
             const int row = idx / UPRW, u = idx % UPRW;
-            if (row < BN) *reinterpret_cast<vec_t *>(Bs + (buf * BN + row) * LSB + u * V) = pb[r];
+            if (row < BN) *reinterpret_cast<vec_t *>(Bs + (buf * BN + row) * LSB + u * V) = src[r];
         }
     };
-    if (RES) {
-#pragma unroll
-        for (int c = 0; c < NCHUNK; ++c) {
-            load_w(c);
-            store_w(c);
-        }
-    }
+    auto load_w = [&](int chunk) { load_w_to(chunk, pb); };
+    auto store_w = [&](int buf) { store_w_from(buf, pb); };
 
     // WDMA: instruction k (0..7) of this wave fills LDS words [(wave + 4k) * 64, +64) of a
     // chunk buffer = rows 4*(wave + 4k) .. +3.  The word a lane delivers depends on k and on
@@ -327,6 +321,20 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     const CopyLane copy_lane = make_copy_lane(64 * TM, tile_pos(next), ep.pool, t);
     if (slot < g.n_ptiles) fetch_patch(next, 0);
     if (WDMA && slot < g.n_ptiles) dma_w(0, 0);
+    // resident weights (at most 48 registers per thread), flips and thresholds: every load is
+    // issued before the first one is waited for, one memory latency for all of them
+    if (RES) {
+        vec_t pall[NCHUNK][STG];
+#pragma unroll
+        for (int c = 0; c < NCHUNK; ++c) load_w_to(c, pall[c]);
+        if (ep.packed) sw = load_step_words<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
+        stage_bias_f32(ep, o_blk, BN, g.c_out, g.k_bits + 1, corr, Ts, t);
+#pragma unroll
+        for (int c = 0; c < NCHUNK; ++c) store_w_from(c, pall[c]);
+    } else {
+        if (ep.packed) sw = load_step_words<TN>(ep, o_blk + wn * TN * 32, l32, g.c_out);
+        stage_bias_f32(ep, o_blk, BN, g.c_out, g.k_bits + 1, corr, Ts, t);
+    }
     int cc = 0;                                            // chunks done so far (WDMA buffer parity)
 
     // The packed words of a tile go to one of two LDS output tiles and are copied to global

@@ -201,38 +201,6 @@ __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int
     const int o_blk = co_tile * 64 * NG;
     const int pw = tw + g.kw - 1, ph = th + g.kh - 1;
 
-    // ---- weights of this block's channels in the K-padded layout, staged once per block.
-    // One thread per (channel, kernel row): its sl source bytes are contiguous in memory and
-    // land at the start of a slp-byte slot whose rest is zero; loads of a slot are issued
-    // together.  The K padding behind the last kernel row is zeroed separately.
-    {
-        const int k_total = g.kh * g.sl;
-        const int nrow = 64 * NG;
-        for (int pair = t; pair < nrow * g.kh; pair += 256) {
-            const int row = div_magic(pair, g.mg_kh), ti = pair - row * g.kh;
-            const int o = o_blk + row;
-            const int8_t *src = wt + (int64_t)o * k_total + ti * g.sl;
-            unsigned char *dst = Wl + row * ws + ti * g.slp;
-            const bool ok = o < g.c_out;
-            for (int b0 = 0; b0 < g.slp; b0 += 16) {
-                int8_t v[16];
-#pragma unroll
-                for (int q = 0; q < 16; ++q) v[q] = (ok && b0 + q < g.sl) ? src[b0 + q] : (int8_t)0;
-                uint4 w4;
-                w4.x = (uint8_t)v[0] | ((uint8_t)v[1] << 8) | ((uint8_t)v[2] << 16) | ((unsigned)(uint8_t)v[3] << 24);
-                w4.y = (uint8_t)v[4] | ((uint8_t)v[5] << 8) | ((uint8_t)v[6] << 16) | ((unsigned)(uint8_t)v[7] << 24);
-                w4.z = (uint8_t)v[8] | ((uint8_t)v[9] << 8) | ((uint8_t)v[10] << 16) | ((unsigned)(uint8_t)v[11] << 24);
-                w4.w = (uint8_t)v[12] | ((uint8_t)v[13] << 8) | ((uint8_t)v[14] << 16) | ((unsigned)(uint8_t)v[15] << 24);
-                *reinterpret_cast<uint4 *>(dst + b0) = w4;
-            }
-        }
-        const int tail0 = g.kh * g.slp, tail = g.kp - tail0;      // multiple of 16 bytes
-        for (int idx = t; idx < nrow * (tail >> 4); idx += 256) {
-            const int row = idx / (tail >> 4), u = idx - row * (tail >> 4);
-            *reinterpret_cast<uint4 *>(Wl + row * ws + tail0 + u * 16) = make_uint4(0u, 0u, 0u, 0u);
-        }
-    }
-
     // ---- this lane's two pixels (window-major rows of the implicit GEMM)
     int pixbyte[2];
 #pragma unroll
@@ -264,14 +232,7 @@ __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int
     }
     const unsigned char *wlane = Wl + l32 * ws + half * 16;     // this lane's bytes of a weight row tile
 
-    // per-channel step parameters, fetched once per block (the first barrier of the tile
-    // loop publishes the accumulator start values; sums stay far below 2^30)
     StepWords<TN> sw[NG];
-    if (ep.packed) {
-#pragma unroll
-        for (int grp = 0; grp < NG; ++grp) sw[grp] = load_step_words<TN>(ep, o_blk + grp * 64, l32, g.c_out);
-    }
-    stage_bias_i32(ep, o_blk, 64 * NG, g.c_out, 1 << 30, Tl, t);
 
     // ---- persistent loop over (image group, tile) work items
     struct Item { int grp, ty, tx; };                   // image group, tile row, tile column
@@ -354,10 +315,49 @@ __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int
     int vn[4];
     Item cur = decode(blockIdx.x < (unsigned)g.n_items ? (int)blockIdx.x : 0), prev = cur, nxt = cur;
     const CopyLane copy_lane = make_copy_lane(256, item_pos(cur), ep.pool, t);
-    if (PIPE && (int)blockIdx.x < g.n_items) {
-        load_bytes_pipe(cur, vn);
-        store_bytes(Pl, 0, vn);
+    // the first patch is requested before the weights, so that their latencies overlap
+    if (PIPE && (int)blockIdx.x < g.n_items) load_bytes_pipe(cur, vn);
+
+    // ---- weights of this block's channels in the K-padded layout, staged once per block.
+    // One thread per (channel, kernel row): its sl source bytes are contiguous in memory and
+    // land at the start of a slp-byte slot whose rest is zero; loads of a slot are issued
+    // together.  The K padding behind the last kernel row is zeroed separately.
+    {
+        const int k_total = g.kh * g.sl;
+        const int nrow = 64 * NG;
+        for (int pair = t; pair < nrow * g.kh; pair += 256) {
+            const int row = div_magic(pair, g.mg_kh), ti = pair - row * g.kh;
+            const int o = o_blk + row;
+            const int8_t *src = wt + (int64_t)o * k_total + ti * g.sl;
+            unsigned char *dst = Wl + row * ws + ti * g.slp;
+            const bool ok = o < g.c_out;
+            for (int b0 = 0; b0 < g.slp; b0 += 16) {
+                int8_t v[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) v[q] = (ok && b0 + q < g.sl) ? src[b0 + q] : (int8_t)0;
+                uint4 w4;
+                w4.x = (uint8_t)v[0] | ((uint8_t)v[1] << 8) | ((uint8_t)v[2] << 16) | ((unsigned)(uint8_t)v[3] << 24);
+                w4.y = (uint8_t)v[4] | ((uint8_t)v[5] << 8) | ((uint8_t)v[6] << 16) | ((unsigned)(uint8_t)v[7] << 24);
+                w4.z = (uint8_t)v[8] | ((uint8_t)v[9] << 8) | ((uint8_t)v[10] << 16) | ((unsigned)(uint8_t)v[11] << 24);
+                w4.w = (uint8_t)v[12] | ((uint8_t)v[13] << 8) | ((uint8_t)v[14] << 16) | ((unsigned)(uint8_t)v[15] << 24);
+                *reinterpret_cast<uint4 *>(dst + b0) = w4;
+            }
+        }
+        const int tail0 = g.kh * g.slp, tail = g.kp - tail0;      // multiple of 16 bytes
+        for (int idx = t; idx < nrow * (tail >> 4); idx += 256) {
+            const int row = idx / (tail >> 4), u = idx - row * (tail >> 4);
+            *reinterpret_cast<uint4 *>(Wl + row * ws + tail0 + u * 16) = make_uint4(0u, 0u, 0u, 0u);
+        }
     }
+
+    // per-channel step parameters, fetched once per block (the first barrier of the tile
+    // loop publishes the accumulator start values; sums stay far below 2^30)
+    if (ep.packed) {
+#pragma unroll
+        for (int grp = 0; grp < NG; ++grp) sw[grp] = load_step_words<TN>(ep, o_blk + grp * 64, l32, g.c_out);
+    }
+    stage_bias_i32(ep, o_blk, 64 * NG, g.c_out, 1 << 30, Tl, t);
+    if (PIPE && (int)blockIdx.x < g.n_items) store_bytes(Pl, 0, vn);
     int it = 0;
     for (int item = blockIdx.x; item < g.n_items; item += gridDim.x, ++it) {
         const unsigned char *Pc = Pl + (PIPE ? (it & 1) * g.patch_bytes : 0);
@@ -574,8 +574,12 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
         g.mg_ph = magic((1 << g.lth) + kh - 1);
         g.mg_kh = magic(kh);
         if (g.kp <= 128 && pbytes <= 24 * 1024) {
-            const bnn_status st = (c_out > 64) ? launch_first_mfma<2>(in, wt, g, ep, s)
-                                               : launch_first_mfma<1>(in, wt, g, ep, s);
+            // two channel groups per block amortise the patch; with too few pixel tiles to fill
+            // the chip (small batches) one group per block doubles the blocks instead
+            const int64_t ptiles = (int64_t)g.tiles_x * g.tiles_y * ((n + g.ni - 1) / g.ni);
+            const bool two_groups = c_out > 64 && ptiles * ((c_out + 127) / 128) >= 256;
+            const bnn_status st = two_groups ? launch_first_mfma<2>(in, wt, g, ep, s)
+                                             : launch_first_mfma<1>(in, wt, g, ep, s);
             if (st != BNN_ERR_UNSUPPORTED) return st;
         }
     }
