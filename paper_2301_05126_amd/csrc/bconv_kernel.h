@@ -231,7 +231,9 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     }
     auto dma_w = [&](int chunk, int buf) {
         const int s0 = chunk * SPC;
-        const unsigned soff0 = (unsigned)(((s0 / WPH) * g.cw + (s0 % WPH)) * 4);
+        // (wave-uniform; read through readfirstlane so that it reaches the transfer's scalar
+        // operand in a scalar register whatever the compiler makes of the chunk index)
+        const unsigned soff0 = (unsigned)__builtin_amdgcn_readfirstlane(((s0 / WPH) * g.cw + (s0 % WPH)) * 4);
         const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) uint32_t *)(Bs + buf * BN * LSB) +
                              (unsigned)__builtin_amdgcn_readfirstlane(wave) * 256u;
 #pragma unroll
