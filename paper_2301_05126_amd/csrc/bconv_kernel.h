@@ -93,6 +93,8 @@ struct ConvGeom {
     int patch_words;             // LDS words of one patch buffer (rounded up)
     int dbuf;                    // 1: two patch buffers, the next tile's patch is fetched during the MFMAs
     unsigned mg_pw, mg_ph;       // ceil(2^32 / d) for d = patch width, patch height (staging index math)
+    int step_group, step_ty, step_tx;    // `slots` pixel tiles as an (image group, tile row, tile column) increment
+    unsigned mg_co, mg_tpg, mg_tx;       // magic_floor of n_co_tiles, tiles per image group, tiles_x
 };
 
 // WPH = words per lane half per tap; the layer's cw words per pixel are zero-padded to 2*WPH.
@@ -147,8 +149,8 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     // an XCD and the patch is fetched from HBM once.
     int bid = blockIdx.x;
     if ((gridDim.x & 7) == 0) bid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int co_tile = bid % g.n_co_tiles;
-    const int slot = bid / g.n_co_tiles;
+    const int slot = div_by(bid, g.n_co_tiles, g.mg_co);
+    const int co_tile = bid - slot * g.n_co_tiles;
     const int th = 1 << g.lth, tw = 1 << g.ltw;
     const int o_blk = co_tile * BN;
     const int pw = tw + 2, ph = th + 2;
@@ -299,11 +301,9 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     // tile coordinates of the previous, current and next pixel tile of this block; a step of
     // `slots` tiles is a fixed (group, y, x) increment with carries
     TileCoord step, prev, cur, next;
-    step.group = g.slots / tiles_per_group;
-    step.ty = (g.slots - step.group * tiles_per_group) / g.tiles_x;
-    step.tx = g.slots - step.group * tiles_per_group - step.ty * g.tiles_x;
-    next.group = slot / tiles_per_group;
-    next.ty = (slot - next.group * tiles_per_group) / g.tiles_x;
+    step.group = g.step_group; step.ty = g.step_ty; step.tx = g.step_tx;
+    next.group = div_by(slot, tiles_per_group, g.mg_tpg);
+    next.ty = div_by(slot - next.group * tiles_per_group, g.tiles_x, g.mg_tx);
     next.tx = slot - next.group * tiles_per_group - next.ty * g.tiles_x;
     prev = cur = next;
     auto advance = [&](TileCoord &c) {
@@ -579,6 +579,13 @@ bool make_geom(int n, int h, int w, int c_in, int c_out, ConvGeom &g, size_t &sm
     if (slots < 1) slots = 1;
     if (slots > g.n_ptiles) slots = g.n_ptiles;
     g.slots = slots;
+    const int tpg = ts.tiles_x * ts.tiles_y;
+    g.step_group = slots / tpg;
+    g.step_ty = (slots - g.step_group * tpg) / ts.tiles_x;
+    g.step_tx = slots - g.step_group * tpg - g.step_ty * ts.tiles_x;
+    g.mg_co = magic_floor(g.n_co_tiles);
+    g.mg_tpg = magic_floor(tpg);
+    g.mg_tx = magic_floor(ts.tiles_x);
     return smem <= (size_t)MAX_SMEM;
 }
 

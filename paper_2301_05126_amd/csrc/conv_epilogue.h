@@ -32,6 +32,17 @@ struct TilePos {
     int img0, y0, x0;        // first image and tile origin of this block
 };
 
+// floor(n / d) for 0 <= n < 2^31 and d >= 1 with mg = magic_floor(d) = floor(2^32 / d) (2^32 - 1 for
+// d == 1): one multiply-high, which is at most one too small, and a correction.  Stands in for the
+// integer divisions of block and tile indices (a run-time division costs some thirty instructions).
+__host__ __device__ __forceinline__ unsigned magic_floor(int d) { return d == 1 ? 0xffffffffu : (unsigned)(0x100000000ULL / (unsigned)d); }
+__device__ __forceinline__ int div_by(int n, int d, unsigned mg)
+{
+    unsigned q = __umulhi((unsigned)n, mg);
+    if ((unsigned)n - q * (unsigned)d >= (unsigned)d) ++q;
+    return (int)q;
+}
+
 // Position of GEMM row `row` (window-major) inside the block's tile.
 __device__ __forceinline__ void row_to_pixel(int row, const TilePos &p, int &img, int &y, int &x)
 {

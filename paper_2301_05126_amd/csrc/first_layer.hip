@@ -154,6 +154,8 @@ struct FirstGeomM {
     int sl, slp, kp;            // bytes of one kernel row, padded to 16, and padded K (multiple of 32)
     int patch_bytes;
     unsigned mg_cin, mg_pw, mg_ph, mg_kh;   // ceil(2^32 / d) for d = c_in, patch width / height, kh
+    int step_grp, step_ty, step_tx;         // a grid's worth of items as an (image group, row, column) increment
+    unsigned mg_tx, mg_ty;                  // magic_floor of tiles_x, tiles_y
 };
 
 // floor(n / d) for n, d < 2^16 with mg = ceil(2^32 / d) (mg == 0 stands for d == 1): one v_mul_hi_u32.
@@ -238,13 +240,15 @@ __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int
     struct Item { int grp, ty, tx; };                   // image group, tile row, tile column
     auto decode = [&](int item) {
         Item c;
-        int rest = item;
-        c.tx = rest % g.tiles_x; rest /= g.tiles_x;
-        c.ty = rest % g.tiles_y; c.grp = rest / g.tiles_y;
+        const int r1 = div_by(item, g.tiles_x, g.mg_tx);
+        c.tx = item - r1 * g.tiles_x;
+        c.grp = div_by(r1, g.tiles_y, g.mg_ty);
+        c.ty = r1 - c.grp * g.tiles_y;
         return c;
     };
     // a step of gridDim.x items is a fixed (group, row, column) increment with carries
-    const Item step = decode((int)gridDim.x);
+    Item step;
+    step.grp = g.step_grp; step.ty = g.step_ty; step.tx = g.step_tx;
     auto advance = [&](Item &c) {
         c.tx += step.tx;
         if (c.tx >= g.tiles_x) { c.tx -= g.tiles_x; ++c.ty; }
@@ -526,6 +530,14 @@ bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, 
     const int64_t cap = 256 * (fast ? 4 : 3);
     const unsigned bx = (unsigned)(items < cap ? items : cap);
     const dim3 grid(bx, (unsigned)g.n_co_tiles);
+    {   // bx items as an (image group, tile row, tile column) increment
+        const int r1 = (int)bx / g.tiles_x;
+        g.step_tx = (int)bx - r1 * g.tiles_x;
+        g.step_grp = r1 / g.tiles_y;
+        g.step_ty = r1 - g.step_grp * g.tiles_y;
+        g.mg_tx = magic_floor(g.tiles_x);
+        g.mg_ty = magic_floor(g.tiles_y);
+    }
     if (fast && ns == 1)
         hipLaunchKernelGGL((conv_first_mfma<NG, true, 1>), grid, dim3(256), smem, s, in, wt, g, ep);
     else if (fast)
