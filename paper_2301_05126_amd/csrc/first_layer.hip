@@ -329,28 +329,34 @@ __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int
     {
         const int k_total = g.kh * g.sl;
         const int nrow = 64 * NG;
+        // Bytes come through a buffer resource over the weight tensor: a channel past c_out
+        // addresses past its end and reads zeros, so the loads need no predicate; the bytes
+        // behind a short kernel row (the next row's weights) are masked off per dword.
+        const __amdgpu_buffer_rsrc_t wr =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(wt), 0, g.c_out * k_total, 0x00020000);
         for (int pair = t; pair < nrow * g.kh; pair += 256) {
             const int row = div_magic(pair, g.mg_kh), ti = pair - row * g.kh;
-            const int o = o_blk + row;
-            const int8_t *src = wt + (int64_t)o * k_total + ti * g.sl;
+            const int base = (o_blk + row) * k_total + ti * g.sl;
             unsigned char *dst = Wl + row * ws + ti * g.slp;
-            const bool ok = o < g.c_out;
             for (int b0 = 0; b0 < g.slp; b0 += 16) {
-                int8_t v[16];
+                unsigned v[16];
 #pragma unroll
-                for (int q = 0; q < 16; ++q) v[q] = (ok && b0 + q < g.sl) ? src[b0 + q] : (int8_t)0;
-                uint4 w4;
-                w4.x = (uint8_t)v[0] | ((uint8_t)v[1] << 8) | ((uint8_t)v[2] << 16) | ((unsigned)(uint8_t)v[3] << 24);
-                w4.y = (uint8_t)v[4] | ((uint8_t)v[5] << 8) | ((uint8_t)v[6] << 16) | ((unsigned)(uint8_t)v[7] << 24);
-                w4.z = (uint8_t)v[8] | ((uint8_t)v[9] << 8) | ((uint8_t)v[10] << 16) | ((unsigned)(uint8_t)v[11] << 24);
-                w4.w = (uint8_t)v[12] | ((uint8_t)v[13] << 8) | ((uint8_t)v[14] << 16) | ((unsigned)(uint8_t)v[15] << 24);
-                *reinterpret_cast<uint4 *>(dst + b0) = w4;
+                for (int q = 0; q < 16; ++q) v[q] = __builtin_amdgcn_raw_buffer_load_b8(wr, base + b0 + q, 0, 0);
+                unsigned w[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int nvalid = g.sl - b0 - 4 * k;          // weight bytes in this dword
+                    const unsigned mask = nvalid >= 4 ? 0xffffffffu : (nvalid <= 0 ? 0u : (1u << (8 * nvalid)) - 1u);
+                    w[k] = (v[4 * k] | (v[4 * k + 1] << 8) | (v[4 * k + 2] << 16) | (v[4 * k + 3] << 24)) & mask;
+                }
+                *reinterpret_cast<uint4 *>(dst + b0) = make_uint4(w[0], w[1], w[2], w[3]);
             }
         }
-        const int tail0 = g.kh * g.slp, tail = g.kp - tail0;      // multiple of 16 bytes
-        for (int idx = t; idx < nrow * (tail >> 4); idx += 256) {
-            const int row = idx / (tail >> 4), u = idx - row * (tail >> 4);
-            *reinterpret_cast<uint4 *>(Wl + row * ws + tail0 + u * 16) = make_uint4(0u, 0u, 0u, 0u);
+        // kp rounds kh * slp (a multiple of 16) up to a multiple of 32: the tail is 0 or 16 bytes
+        const int tail0 = g.kh * g.slp;
+        if (g.kp > tail0) {
+            for (int row = t; row < nrow; row += 256)
+                *reinterpret_cast<uint4 *>(Wl + row * ws + tail0) = make_uint4(0u, 0u, 0u, 0u);
         }
     }
 
@@ -585,7 +591,8 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
         g.mg_pw = magic((1 << g.ltw) + kw - 1);
         g.mg_ph = magic((1 << g.lth) + kh - 1);
         g.mg_kh = magic(kh);
-        if (g.kp <= 128 && pbytes <= 24 * 1024) {
+        // (the weight tensor is addressed with 32-bit byte offsets)
+        if (g.kp <= 128 && pbytes <= 24 * 1024 && (int64_t)c_out * kh * g.sl < 0x7fffffffLL) {
             // two channel groups per block amortise the patch; with too few pixel tiles to fill
             // the chip (small batches) one group per block doubles the blocks instead
             const int64_t ptiles = (int64_t)g.tiles_x * g.tiles_y * ((n + g.ni - 1) / g.ni);
