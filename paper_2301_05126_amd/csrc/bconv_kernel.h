@@ -166,28 +166,44 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
     // (half, step) is W[o][tap][half*WPH + cwi] with tap = step / WPH, cwi = step % WPH.
     vec_t pb[STG];
     const bool wvec_ok = (g.cw % V) == 0;
+    // A thread's units keep their row and position inside the chunk; per chunk only a uniform
+    // (tap, word) offset is added.  (step = chunk * SPC + vg * V splits into a chunk part and a
+    // unit part without carry because SPC is a multiple of WPH or the other way round.)
+    static_assert(SPC % WPH == 0 || WPH % SPC == 0, "chunk and unit parts of a step index add without carry");
+    int wu_off[STG], wu_cw[STG];                       // word offset / word inside the pixel, chunk 0
+    bool wu_row[STG];
+    if (!WDMA) {
+#pragma unroll
+        for (int r = 0; r < STG; ++r) {
+            const int idx = t + 256 * r;
+            const int row = idx / UPRW, u = idx % UPRW;
+            const int hh = u / NVG, s0 = (u % NVG) * V;
+            const int tapr = WPH <= SPC ? s0 / WPH : 0, cwir = WPH <= SPC ? s0 % WPH : s0;
+            const int o = o_blk + row;
+            wu_row[r] = row < BN && o < g.c_out;
+            wu_cw[r] = hh * WPH + cwir;
+            wu_off[r] = (o * 9 + tapr) * g.cw + wu_cw[r];
+        }
+    }
     auto load_w_to = [&](int chunk, vec_t (&dst)[STG]) {
         // Branch-free inside each loop, so that all loads of a chunk are in flight together:
         // rows or words that do not exist read the first weight word and are zeroed afterwards.
+        const int sc = chunk * SPC;
+        const int cwic = sc % WPH;
+        const int coff = (sc / WPH) * g.cw + cwic;
         auto unit = [&](int r, bool &row_ok, int &cwpos) {
-            const int idx = t + 256 * r;
-            const int row = idx / UPRW, u = idx % UPRW;
-            const int hh = u / NVG, vg = u % NVG;
-            const int s = chunk * SPC + vg * V;
-            const int tap = s / WPH, cwi = s % WPH;
-            cwpos = hh * WPH + cwi;
-            const int o = o_blk + row;
-            row_ok = row < BN && o < g.c_out;
-            return wt + ((int64_t)o * 9 + tap) * g.cw + cwpos;
+            cwpos = wu_cw[r] + cwic;
+            row_ok = wu_row[r];
+            return wu_off[r] + coff;
         };
         if (wvec_ok) {
 #pragma unroll
             for (int r = 0; r < STG; ++r) {
                 bool row_ok;
                 int cwpos;
-                const uint32_t *src = unit(r, row_ok, cwpos);
+                const int off = unit(r, row_ok, cwpos);
                 const bool ok = row_ok && cwpos < g.cw;
-                vec_t v = *reinterpret_cast<const vec_t *>(ok ? src : wt);
+                vec_t v = *reinterpret_cast<const vec_t *>(wt + (unsigned)(ok ? off : 0));
 #pragma unroll
                 for (int q = 0; q < V; ++q) vec_set(v, q, ok ? vec_word(v, q) : 0u);
                 dst[r] = v;
@@ -197,12 +213,12 @@ void bconv_mfma(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt
             for (int r = 0; r < STG; ++r) {
                 bool row_ok;
                 int cwpos;
-                const uint32_t *src = unit(r, row_ok, cwpos);
+                const int off = unit(r, row_ok, cwpos);
                 vec_t v;
 #pragma unroll
                 for (int q = 0; q < V; ++q) {
                     const bool ok = row_ok && cwpos + q < g.cw;
-                    const uint32_t x = *(ok ? src + q : wt);
+                    const uint32_t x = wt[(unsigned)(ok ? off + q : 0)];
                     vec_set(v, q, ok ? x : 0u);
                 }
                 dst[r] = v;
@@ -564,6 +580,7 @@ bool make_geom(int n, int h, int w, int c_in, int c_out, ConvGeom &g, size_t &sm
     g.n_co_tiles = (c_out + 64 * TN - 1) / (64 * TN);
     const int64_t ptiles = (int64_t)ts.tiles_x * ts.tiles_y * ((n + ts.ni - 1) / ts.ni);
     if (ptiles > 0x3fffffffLL || (int64_t)ts.ni * h * w * g.cw * 4 >= 0x7fffffffLL) return false;
+    if (((int64_t)c_out + 64 * TN) * 9 * g.cw >= 0x7fffffffLL) return false;     // 32-bit weight word offsets
     g.n_ptiles = (int)ptiles;
     // exact for dividends below 2^16 (a patch has at most a few thousand units)
     g.mg_pw = (unsigned)((0x100000000ULL + (1 << ts.ltw) + 1) / ((1 << ts.ltw) + 2));
