@@ -12,6 +12,7 @@ LIB = os.path.join(PKG, "libbnn.so")
 
 # (source, extra defines, object name)
 UNITS = [("bnn_api.hip", [], "bnn_api.o"), ("bgemm.hip", [], "bgemm.o"), ("bconv.hip", [], "bconv.o"),
+         ("bconv_small.hip", [], "bconv_small.o"),
          ("first_layer.hip", [], "first_layer.o"), ("elementwise.hip", [], "elementwise.o"),
          ("host_tools.hip", [], "host_tools.o")]
 # the convolution kernels: per channel-word width, the 256 x 128 tile (part 1, slowest) apart

@@ -1,5 +1,7 @@
-// Binary 3x3 convolution: host-side dispatch to the kernel set for the layer's channel width.
-// The kernels live in bconv_kernel.h and are instantiated by bconv_inst.hip.
+// Binary 3x3 convolution: host-side dispatch to the small-problem kernel (bconv_small.hip) or to
+// the tile kernel set for the layer's channel width (bconv_kernel.h, instantiated by bconv_inst.hip).
+#include <stdlib.h>
+
 #include "bnn_internal.h"
 
 namespace bnn {
@@ -25,6 +27,14 @@ bnn_status launch_conv_binary(const uint32_t *in, int n, int h, int w, int c_in,
                               int c_out, const EpiArgs &ep, hipStream_t s)
 {
     if (n == 0) return BNN_OK;
+    // a handful of images: the latency kernel (one block per 32 pixels x 32 channels), unless the
+    // environment asks for the tile kernels (BNN_CONV_TILES_ONLY=1: lets tests reach them with
+    // small shapes)
+    const char *tiles_only = getenv("BNN_CONV_TILES_ONLY");
+    if (!(tiles_only && tiles_only[0] && tiles_only[0] != '0')) {
+        const bnn_status small = launch_conv_binary_small(in, n, h, w, c_in, wt, c_out, ep, s);
+        if (small != BNN_ERR_UNSUPPORTED) return small;
+    }
     // words per lane half per tap: channel words per pixel rounded up to 2, 4, 8, 16 or 32
     const int cw = (c_in + 31) / 32;
     int wph = 1;

@@ -1,0 +1,175 @@
+// Binary 3x3 convolution for problems too small to fill the chip with the persistent tile
+// kernels (a few images): latency, not throughput, is what counts there, and a block of the
+// tile kernels runs its K loop on one wave per SIMD.  Here a block owns 32 output pixels x 32
+// output channels and its four waves split K: wave v takes the MFMA steps v, v + 4, ... (a step
+// = 64 bits of K = one channel word per lane half of one tap), reads its operand words straight
+// from global memory (all loads in flight together with the thresholds and flips, no staging),
+// and the partial sums meet in LDS.  (Eight waves per block were measured and are not faster.)  Wave 0 then runs the same step / pool / pack epilogue as the tile kernels.
+// Same conventions: pixels in window-major order, weights as the MFMA's first matrix (rows =
+// channels, lanes = pixels), out-of-image taps = -1 = zero bits, FP4 +-1 operands.
+#include "bnn_internal.h"
+#include "conv_epilogue.h"
+#include "lds_dma.h"
+
+namespace bnn {
+
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+struct SmallGeom {
+    int n, h, w, cw, c_out, k_bits;
+    int lth, ltw, ni, tiles_x, tiles_y, n_co_tiles;
+    unsigned mg_co, mg_tpg, mg_tx;       // magic_floor of n_co_tiles, tiles per image group, tiles_x
+};
+
+// WPH = channel words per lane half per tap; the layer has exactly 2 * WPH words per pixel.
+template <int WPH>
+__global__ __launch_bounds__(256) void bconv_small(const uint32_t *__restrict__ in, const uint32_t *__restrict__ wt,
+                                                   SmallGeom g, EpiArgs ep)
+{
+    constexpr int NW = 4;                // waves of the block
+    __shared__ float red[NW - 1][16][64];    // partial sums of waves 1..NW-1
+    __shared__ uint32_t outw[32];        // the tile's packed words, one per output pixel
+    constexpr int S = 9 * WPH;           // MFMA steps of the whole K
+    constexpr int NS = (S + NW - 1) / NW;    // steps per wave (the last one may be missing)
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const int ptile = div_by((int)blockIdx.x, g.n_co_tiles, g.mg_co);
+    const int o0 = ((int)blockIdx.x - ptile * g.n_co_tiles) * 32;
+    const int tpg = g.tiles_x * g.tiles_y;
+    const int group = div_by(ptile, tpg, g.mg_tpg);
+    const int ty = div_by(ptile - group * tpg, g.tiles_x, g.mg_tx);
+    const int tx = ptile - group * tpg - ty * g.tiles_x;
+    TilePos pos;
+    pos.n = g.n; pos.h = g.h; pos.w = g.w; pos.c_out = g.c_out;
+    pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = group * g.ni; pos.y0 = ty << g.lth; pos.x0 = tx << g.ltw;
+
+    // this lane's pixel (MFMA column) and channel (MFMA row of the weight operand)
+    int img, y, x;
+    row_to_pixel(l32, pos, img, y, x);
+    const bool pix_ok = img < g.n && y < g.h && x < g.w;
+    const int o = o0 + l32;
+    const bool ch_ok = o < g.c_out;
+
+    // operand words of this wave's steps: branch-free, so that all loads are in flight together
+    // (a word that does not exist reads word 0 of its tensor and is zeroed)
+    uint32_t aw[NS], bw[NS];
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        const int s = wave + NW * k;
+        const int tap = s / WPH, cwi = s % WPH;
+        const int ti = tap / 3, tj = tap - 3 * ti;
+        const int yy = y + ti - 1, xx = x + tj - 1;
+        const bool a_ok = s < S && pix_ok && yy >= 0 && yy < g.h && xx >= 0 && xx < g.w;
+        const bool b_ok = s < S && ch_ok;
+        const uint32_t av = in[(unsigned)(a_ok ? ((img * g.h + yy) * g.w + xx) * g.cw + half * WPH + cwi : 0)];
+        const uint32_t bv = wt[(unsigned)(b_ok ? (o * 9 + tap) * g.cw + half * WPH + cwi : 0)];
+        aw[k] = a_ok ? av : 0u;
+        bw[k] = b_ok ? bv : 0u;
+    }
+
+    // wave 0's epilogue parameters, requested now so that they arrive with the operands
+    int th[16];
+    StepWords<1> sw;
+    if (wave == 0 && ep.packed) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int c = o0 + (r >> 2) * 8 + half * 4 + (r & 3);
+            th[r] = ep.thr[c < g.c_out ? c : 0];
+        }
+        sw = load_step_words<1>(ep, o0, l32, g.c_out);
+    }
+
+    uint32_t sgn = 0x88888888u, one = 0x22222222u;
+    asm volatile("" : "+s"(sgn));
+    asm volatile("" : "+v"(one));
+    v16f acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        if (wave + NW * k < S) {         // uniform per wave
+            const v8i a = expand_fp4(aw[k], sgn, one), b = expand_fp4(bw[k], sgn, one);
+            acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, acc, 4, 4, 0, 0, 0, 0);
+        }
+    }
+
+    // ---- the partial sums meet in wave 0 (all values are small integers: exact)
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[wave - 1][r][lane] = acc[r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+#pragma unroll
+            for (int v = 0; v < NW - 1; ++v) acc[r] += red[v][r][lane];
+
+        if (ep.preact) {
+            auto getx = [&](int, int, int r) { return (int)acc[r]; };
+            conv_tile_store_preact<1, 1>(getx, 0, o0, l32, half, pos, ep.preact);
+        }
+        if (ep.packed) {
+            // x - T - 1/2: never zero, negative exactly when x <= T (T clamped to +-(K + 1))
+            const int bound = g.k_bits + 1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int tc = th[r] > bound ? bound : (th[r] < -bound ? -bound : th[r]);
+                acc[r] -= (float)tc + 0.5f;
+            }
+            auto gets = [&](int, int, int r) { return acc[r]; };
+            conv_tile_step_to_lds<1, 1>(gets, 0, 0, 1, l32, half, sw, ep.pool, ep.pool_first != 0, outw);
+        }
+    }
+    if (ep.packed) {
+        __syncthreads();
+        const CopyLane cl = make_copy_lane(32, pos, ep.pool, t);
+        conv_tile_copy_out<1>(outw, cl, o0 >> 5, pos, ep);
+    }
+}
+
+template <int WPH>
+bnn_status launch_small(const uint32_t *in, const uint32_t *wt, const SmallGeom &g, unsigned blocks,
+                        const EpiArgs &ep, hipStream_t s)
+{
+    hipLaunchKernelGGL((bconv_small<WPH>), dim3(blocks), dim3(256), 0, s, in, wt, g, ep);
+    return hip_result(hipGetLastError());
+}
+
+}  // namespace
+
+// Runs the layer on the small-problem kernel if it qualifies: exactly 2 * WPH channel words per
+// pixel (C_in a multiple of 64 with a power-of-two word count) and at most one block per compute
+// unit.  Returns BNN_ERR_UNSUPPORTED otherwise (the caller then takes the tile kernels).
+bnn_status launch_conv_binary_small(const uint32_t *in, int n, int h, int w, int c_in, const uint32_t *wt,
+                                    int c_out, const EpiArgs &ep, hipStream_t s)
+{
+    const int cw = (c_in + 31) / 32;
+    if ((c_in & 63) != 0 || (cw & (cw - 1)) != 0 || cw > 32) return BNN_ERR_UNSUPPORTED;
+    const TileShape ts = make_tile_shape(h, w, 32);
+    const int64_t ptiles = (int64_t)ts.tiles_x * ts.tiles_y * ((n + ts.ni - 1) / ts.ni);
+    const int n_co = (c_out + 31) / 32;
+    if (ptiles * n_co > 256) return BNN_ERR_UNSUPPORTED;
+    SmallGeom g;
+    g.n = n; g.h = h; g.w = w; g.cw = cw; g.c_out = c_out; g.k_bits = 9 * c_in;
+    g.lth = ts.lth; g.ltw = ts.ltw; g.ni = ts.ni; g.tiles_x = ts.tiles_x; g.tiles_y = ts.tiles_y;
+    g.n_co_tiles = n_co;
+    g.mg_co = magic_floor(n_co);
+    g.mg_tpg = magic_floor(ts.tiles_x * ts.tiles_y);
+    g.mg_tx = magic_floor(ts.tiles_x);
+    const unsigned blocks = (unsigned)(ptiles * n_co);
+    switch (cw) {
+    case 2: return launch_small<1>(in, wt, g, blocks, ep, s);
+    case 4: return launch_small<2>(in, wt, g, blocks, ep, s);
+    case 8: return launch_small<4>(in, wt, g, blocks, ep, s);
+    case 16: return launch_small<8>(in, wt, g, blocks, ep, s);
+    case 32: return launch_small<16>(in, wt, g, blocks, ep, s);
+    }
+    return BNN_ERR_UNSUPPORTED;
+}
+
+}  // namespace bnn

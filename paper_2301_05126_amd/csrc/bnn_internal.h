@@ -39,6 +39,10 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
                                   const int8_t *wt, int c_out, int kh, int kw, int pad,
                                   int pad_value, const EpiArgs &ep, hipStream_t s);
 
+// The small-problem kernel of launch_conv_binary; BNN_ERR_UNSUPPORTED if the layer does not qualify.
+bnn_status launch_conv_binary_small(const uint32_t *in, int n, int h, int w, int c_in,
+                                    const uint32_t *wt, int c_out, const EpiArgs &ep, hipStream_t s);
+
 // Whether launch_conv_binary can run this shape (LDS budget of the input patch).
 bool conv_binary_supported(int h, int w, int c_in);
 

@@ -126,7 +126,9 @@ CONV_SHAPES = [(1, 4, 4, 32, 8, 1), (2, 8, 8, 64, 64, 2), (3, 14, 14, 64, 64, 2)
                (2, 3, 3, 96, 130, 1), (1, 1, 1, 32, 32, 1), (3, 2, 2, 64, 16, 2), (2, 6, 6, 40, 24, 1),
                (3, 4, 4, 512, 512, 2), (1, 20, 36, 128, 64, 2), (17, 4, 4, 128, 128, 1),
                (2, 4, 4, 1024, 64, 2), (1, 6, 6, 608, 96, 1), (40, 8, 8, 256, 256, 2), (2, 2, 6, 32, 300, 1),
-               (600, 2, 2, 64, 64, 2), (9, 16, 16, 64, 128, 2)]
+               (600, 2, 2, 64, 64, 2), (9, 16, 16, 64, 128, 2),
+               # ragged pixel tiles and channel tiles with C_in a multiple of 64 (small-problem kernel)
+               (1, 5, 7, 64, 40, 1), (2, 6, 10, 128, 96, 2), (1, 3, 9, 256, 33, 1), (3, 2, 18, 64, 70, 2)]
 
 
 def extreme_thresholds(thr, room, k):
@@ -141,9 +143,15 @@ def conv_weights_packed(wt):
     return pack_pm1(wt.reshape(co * 9, ci)).reshape(co, 3, 3, (ci + 31) // 32)
 
 
+@pytest.mark.parametrize("path", ["auto", "tiles"])
 @pytest.mark.parametrize("n,h,w,ci,co,pool", CONV_SHAPES)
-def test_conv_binary_raw_and_fused(n, h, w, ci, co, pool):
-    print("conv", n, h, w, ci, co, pool, flush=True)
+def test_conv_binary_raw_and_fused(n, h, w, ci, co, pool, path, monkeypatch):
+    # "tiles": the tile kernels also for shapes that would take the small-problem kernel
+    if path == "tiles":
+        monkeypatch.setenv("BNN_CONV_TILES_ONLY", "1")
+    else:
+        monkeypatch.delenv("BNN_CONV_TILES_ONLY", raising=False)
+    print("conv", path, n, h, w, ci, co, pool, flush=True)
     rng = rng_of(n + h * 3 + w * 5 + ci * 7 + co * 11)
     x, wt = pm1(rng, (n, h, w, ci)), pm1(rng, (co, 3, 3, ci))
     want = oracle.conv2d(x, wt, 1, -1)
