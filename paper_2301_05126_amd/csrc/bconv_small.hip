@@ -1,8 +1,9 @@
 // Binary 3x3 convolution for problems too small to fill the chip with the persistent tile
 // kernels (a few images): latency, not throughput, is what counts there, and a block of the
 // tile kernels runs its K loop on one wave per SIMD.  Here a block owns 32 output pixels x 32
-// output channels and its four waves split K: wave v takes the MFMA steps v, v + 4, ... (a step
-// = 64 bits of K = one channel word per lane half of one tap), reads its operand words straight
+// output channels and its four waves split K in units of up to four MFMA steps (a step = 64 bits
+// of K = one channel word per lane half of one tap; a unit = consecutive words of one tap, one
+// vector load per operand): wave v takes the units v, v + 4, ..., reads its operand words straight
 // from global memory (all loads in flight together with the thresholds and flips, no staging),
 // and the partial sums meet in LDS.  (Eight waves per block were measured and are not faster.)  Wave 0 then runs the same step / pool / pack epilogue as the tile kernels.
 // Same conventions: pixels in window-major order, weights as the MFMA's first matrix (rows =
@@ -31,8 +32,10 @@ __global__ __launch_bounds__(256) void bconv_small(const uint32_t *__restrict__ 
     constexpr int NW = 4;                // waves of the block
     __shared__ float red[NW - 1][16][64];    // partial sums of waves 1..NW-1
     __shared__ uint32_t outw[32];        // the tile's packed words, one per output pixel
-    constexpr int S = 9 * WPH;           // MFMA steps of the whole K
-    constexpr int NS = (S + NW - 1) / NW;    // steps per wave (the last one may be missing)
+    constexpr int UW = WPH < 4 ? WPH : 4;    // words (= steps) per unit
+    constexpr int UPT = WPH / UW;            // units per tap
+    constexpr int NU = 9 * UPT;              // units of the whole K
+    constexpr int NUW = (NU + NW - 1) / NW;  // units per wave (the last one may be missing)
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -54,21 +57,35 @@ __global__ __launch_bounds__(256) void bconv_small(const uint32_t *__restrict__ 
     const int o = o0 + l32;
     const bool ch_ok = o < g.c_out;
 
-    // operand words of this wave's steps: branch-free, so that all loads are in flight together
-    // (a word that does not exist reads word 0 of its tensor and is zeroed)
-    uint32_t aw[NS], bw[NS];
+    // operand words of this wave's units: branch-free, so that all loads are in flight together
+    // (a unit that does not exist reads the start of its tensor and is zeroed)
+    uint32_t aw[NUW][UW], bw[NUW][UW];
+    auto load_unit = [&](const uint32_t *p, uint32_t (&dst)[UW]) {
+        if constexpr (UW == 4) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(p);
+            dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+        } else if constexpr (UW == 2) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(p);
+            dst[0] = v.x; dst[1] = v.y;
+        } else {
+            dst[0] = *p;
+        }
+    };
 #pragma unroll
-    for (int k = 0; k < NS; ++k) {
-        const int s = wave + NW * k;
-        const int tap = s / WPH, cwi = s % WPH;
+    for (int k = 0; k < NUW; ++k) {
+        const int u = wave + NW * k;
+        const int tap = u / UPT, cw0 = (u % UPT) * UW;
         const int ti = tap / 3, tj = tap - 3 * ti;
         const int yy = y + ti - 1, xx = x + tj - 1;
-        const bool a_ok = s < S && pix_ok && yy >= 0 && yy < g.h && xx >= 0 && xx < g.w;
-        const bool b_ok = s < S && ch_ok;
-        const uint32_t av = in[(unsigned)(a_ok ? ((img * g.h + yy) * g.w + xx) * g.cw + half * WPH + cwi : 0)];
-        const uint32_t bv = wt[(unsigned)(b_ok ? (o * 9 + tap) * g.cw + half * WPH + cwi : 0)];
-        aw[k] = a_ok ? av : 0u;
-        bw[k] = b_ok ? bv : 0u;
+        const bool a_ok = u < NU && pix_ok && yy >= 0 && yy < g.h && xx >= 0 && xx < g.w;
+        const bool b_ok = u < NU && ch_ok;
+        load_unit(in + (unsigned)(a_ok ? ((img * g.h + yy) * g.w + xx) * g.cw + half * WPH + cw0 : 0), aw[k]);
+        load_unit(wt + (unsigned)(b_ok ? (o * 9 + tap) * g.cw + half * WPH + cw0 : 0), bw[k]);
+#pragma unroll
+        for (int q = 0; q < UW; ++q) {
+            aw[k][q] = a_ok ? aw[k][q] : 0u;
+            bw[k][q] = b_ok ? bw[k][q] : 0u;
+        }
     }
 
     // wave 0's epilogue parameters, requested now so that they arrive with the operands
@@ -90,10 +107,13 @@ __global__ __launch_bounds__(256) void bconv_small(const uint32_t *__restrict__ 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
-    for (int k = 0; k < NS; ++k) {
-        if (wave + NW * k < S) {         // uniform per wave
-            const v8i a = expand_fp4(aw[k], sgn, one), b = expand_fp4(bw[k], sgn, one);
-            acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, acc, 4, 4, 0, 0, 0, 0);
+    for (int k = 0; k < NUW; ++k) {
+        if (wave + NW * k < NU) {        // uniform per wave
+#pragma unroll
+            for (int q = 0; q < UW; ++q) {
+                const v8i a = expand_fp4(aw[k][q], sgn, one), b = expand_fp4(bw[k][q], sgn, one);
+                acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, acc, 4, 4, 0, 0, 0, 0);
+            }
         }
     }
 
