@@ -122,7 +122,7 @@ bnn_status bnn_conv_first_int8(const int8_t *in_dev, int n, int h, int w, int c_
  *   Outputs as for bnn_conv_first_int8 (ho = h, wo = w).
  * Errors: NULL, SHAPE, ALIGN, UNSUPPORTED (c_in > 1024, or one image's packed input of
  *         2 GiB or more).
- * Layers of at most 256 tiles of 32 pixels x 32 channels (a few images) with c_in in
+ * Layers of at most 1024 tiles of 32 pixels x 32 channels (a few images) with c_in in
  * {64, 128, 256, 512, 1024} run on a latency kernel, everything else on the persistent tile
  * kernels; the environment variable BNN_CONV_TILES_ONLY=1 (read at every call) selects the
  * tile kernels for all shapes.  Results are identical.
