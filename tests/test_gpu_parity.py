@@ -128,7 +128,9 @@ CONV_SHAPES = [(1, 4, 4, 32, 8, 1), (2, 8, 8, 64, 64, 2), (3, 14, 14, 64, 64, 2)
                (2, 4, 4, 1024, 64, 2), (1, 6, 6, 608, 96, 1), (40, 8, 8, 256, 256, 2), (2, 2, 6, 32, 300, 1),
                (600, 2, 2, 64, 64, 2), (9, 16, 16, 64, 128, 2),
                # ragged pixel tiles and channel tiles with C_in a multiple of 64 (small-problem kernel)
-               (1, 5, 7, 64, 40, 1), (2, 6, 10, 128, 96, 2), (1, 3, 9, 256, 33, 1), (3, 2, 18, 64, 70, 2)]
+               (1, 5, 7, 64, 40, 1), (2, 6, 10, 128, 96, 2), (1, 3, 9, 256, 33, 1), (3, 2, 18, 64, 70, 2),
+               # exactly at and just past the small-problem kernel's limit of 1024 tiles
+               (128, 8, 8, 64, 128, 2), (129, 8, 8, 64, 128, 1)]
 
 
 def extreme_thresholds(thr, room, k):
