@@ -8,7 +8,12 @@
  * an execution backend: run a given model layer by layer on a batch, return the class
  * scores and each layer's device time next to its host-core time.
  *
- * Data conventions (all integer; there is no floating point on the path)
+ * Data conventions.  Every input, output and intermediate tensor is an integer or a bit.  The
+ * dense binary layers multiply on the matrix cores with +-1 operands held as FP4 (E2M1) values
+ * and FP32 accumulators; all their sums are integers (or odd multiples of 1/2) of magnitude
+ * below 2^24, which FP32 holds exactly, so every result equals the integer definition bit for
+ * bit.  The first layer uses int8 operands with int32 accumulators, batch <= 8 FC layers use
+ * xor + popcount on the vector ALU.
  *   - +1/-1 values are stored one bit each: bit 1 = +1, bit 0 = -1.
  *   - packed vectors: element t lives in 32-bit word t/32 at bit t%32 (LSB first); a row of
  *     k elements takes ceil(k/32) words and the unused high bits of its last word are 0.
@@ -116,16 +121,19 @@ bnn_status bnn_conv_first_int8(const int8_t *in_dev, int n, int h, int w, int c_
 /*
  * Binary 3x3 convolution, stride 1, one ring of padding whose value is -1 (bit 0), so
  * every output sums exactly K = 9*c_in products (paper Sec. II-A: neuron output
- * 2*popcount(xnor(W, I)) - #bits; evaluated here as K - 2*popcount(W xor I)).
+ * 2*popcount(xnor(W, I)) - #bits, i.e. the sum of the K products of +-1 values; evaluated here
+ * as that sum on the matrix cores, bits expanded to FP4 +-1.0, FP32 accumulators, exact).
  *   in_dev: device, packed uint32 [n][h][w][ceil(c_in/32)].
  *   w_dev:  device, packed uint32 [c_out][3][3][ceil(c_in/32)].
+ *   When c_in % 32 != 0 the unused high bits of every pixel's and every tap's last word must be
+ *   0 in both operands (bnn_pack_bits and the fused epilogues write them as 0); they are
+ *   counted as matching pairs and the constant is subtracted.
  *   Outputs as for bnn_conv_first_int8 (ho = h, wo = w).
  * Errors: NULL, SHAPE, ALIGN, UNSUPPORTED (c_in > 1024, or one image's packed input of
  *         2 GiB or more).
  * Layers of at most 1024 tiles of 32 pixels x 32 channels (a few images) with c_in in
  * {64, 128, 256, 512, 1024} run on a latency kernel, everything else on the persistent tile
- * kernels; the environment variable BNN_CONV_TILES_ONLY=1 (read at every call) selects the
- * tile kernels for all shapes.  Results are identical.
+ * kernels; the choice depends on the shape only and the results are identical.
  */
 bnn_status bnn_conv_binary(const uint32_t *in_dev, int n, int h, int w, int c_in,
                            const uint32_t *w_dev, int c_out, const bnn_epilogue *ep,
@@ -133,14 +141,17 @@ bnn_status bnn_conv_binary(const uint32_t *in_dev, int n, int h, int w, int c_in
 
 /*
  * Binary fully-connected layer / binary GEMM (paper Sec. II-A fully-connected layer):
- *   C[r][o] = K - 2 * sum_words popcount(A[r][.] xor B[o][.])  ( = sum_t a[r][t]*b[o][t] )
+ *   C[r][o] = sum_t a[r][t]*b[o][t]  ( = K - 2 * sum_words popcount(A[r][.] xor B[o][.]) )
+ *   m > 8: matrix cores (FP4 +-1.0 operands, FP32 accumulators, exact for the K accepted);
+ *   m <= 8: xor + popcount on the vector ALU (bandwidth bound).
  *   a_dev: device, packed uint32 [m][ceil(k/32)]  (row-major along K)
  *   b_dev: device, packed uint32 [n][ceil(k/32)]  (each output's K bits contiguous)
  *   ep == NULL: c_out_dev (int32 [m][n]) required.
  *   ep != NULL: ep->pool must be 1; packed_out_dev (uint32 [m][ceil(n/32)]) required,
  *               c_out_dev optional.
  * Tail bits of both operands' last words must be 0 (bnn_pack_bits guarantees it).
- * Errors: NULL, SHAPE, ALIGN.
+ * Errors: NULL, SHAPE (also k > 2^30), ALIGN, UNSUPPORTED (m > 8 and k > 2^24 - 2048: the
+ *         FP32 accumulators of the matrix-core path would no longer be exact).
  */
 bnn_status bnn_fc_binary(const uint32_t *a_dev, int64_t m, int64_t k, const uint32_t *b_dev,
                          int64_t n, const bnn_epilogue *ep, int32_t *c_out_dev,

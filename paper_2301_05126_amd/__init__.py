@@ -1,5 +1,7 @@
-"""libbnn for MI355X: binarized-network layers (xor + popcount conv / FC over bit-packed
-+-1 operands, integer sign thresholds, max-pool) behind a C ABI, with a thin ctypes binding.
+"""libbnn for MI355X: binarized-network layers (conv / FC over bit-packed +-1 operands, integer
+sign thresholds, max-pool) behind a C ABI, with a thin ctypes binding.  The dense layers
+expand the packed bits to FP4 +-1.0 in registers and multiply on the matrix cores with exact
+FP32 accumulators; batch <= 8 FC layers use xor + popcount on the vector ALU.
 
 Every step of the path runs in the HIP kernels of libbnn.so; this package only marshals
 arguments.  There is no CPU fallback: importing the package raises if the shared library has

@@ -19,6 +19,11 @@ bnn_status BNN_CAT(launch_conv_binary_wph, BNN_CONV_WPH)(const uint32_t *in, int
 {
     return launch_wph<BNN_CONV_WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
 }
+
+int BNN_CAT(conv_tile_choice_wph, BNN_CONV_WPH)(int n, int h, int w, int c_in, int c_out)
+{
+    return tile_choice_wph<BNN_CONV_WPH>(n, h, w, c_in, c_out);
+}
 #else
 template <>
 bnn_status launch_conv_big_tile<BNN_CONV_WPH>(const uint32_t *in, const uint32_t *wt, int n, int h, int w,

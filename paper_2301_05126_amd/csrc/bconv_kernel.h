@@ -23,6 +23,8 @@
 // conv_epilogue.h.
 #ifndef BNN_BCONV_KERNEL_H
 #define BNN_BCONV_KERNEL_H
+#include <mutex>
+
 #include "bnn_internal.h"
 #include "conv_epilogue.h"
 #include "lds_dma.h"
@@ -614,14 +616,16 @@ bnn_status launch_one(const uint32_t *in, const uint32_t *wt, int n, int h, int 
     size_t smem;
     if (!make_geom<TM, TN, WPH, WDMA>(n, h, w, c_in, c_out, g, smem)) return BNN_ERR_UNSUPPORTED;
     const unsigned blocks = (unsigned)(g.slots * g.n_co_tiles);
-    if (smem > 64 * 1024) {          // above the default limit of dynamic LDS: opt in once
-        static bool raised = false;
-        if (!raised) {
-            const bnn_status e = hip_result(hipFuncSetAttribute((const void *)bconv_mfma<TM, TN, WPH, WDMA>,
-                                                                hipFuncAttributeMaxDynamicSharedMemorySize, MAX_SMEM));
-            if (e != BNN_OK) return e;
-            raised = true;
-        }
+    if (smem > 64 * 1024) {          // above the default limit of dynamic LDS: opt in, once per kernel
+        // (callers on distinct threads may arrive here together; a failed attempt is reported to
+        // every caller of this kernel, a successful one is never repeated)
+        static std::once_flag once;
+        static hipError_t raise_err = hipSuccess;
+        std::call_once(once, [] {
+            raise_err = hipFuncSetAttribute((const void *)bconv_mfma<TM, TN, WPH, WDMA>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, MAX_SMEM);
+        });
+        if (raise_err != hipSuccess) return hip_result(raise_err);
     }
     hipLaunchKernelGGL((bconv_mfma<TM, TN, WPH, WDMA>), dim3(blocks), dim3(256), smem, s, in, wt, g, ep);
     return hip_result(hipGetLastError());
@@ -649,19 +653,31 @@ bnn_status launch_conv_big_tile(const uint32_t *in, const uint32_t *wt, int n, i
 
 namespace {
 
+// Which block tile launch_wph takes: the largest that fits LDS and still gives two resident
+// blocks per compute unit.  3: 256 x 128, 2: 128 x 128 with streamed weights, 1: 128 x 128,
+// 0: 64 x 64.
 template <int WPH>
-bnn_status launch_wph(const uint32_t *in, const uint32_t *wt, int n, int h, int w, int c_in, int c_out,
-                      const EpiArgs &ep, hipStream_t s)
+int tile_choice_wph(int n, int h, int w, int c_in, int c_out)
 {
     const int64_t want = 512;     // two resident blocks per compute unit
     // the largest tile keeps its weights resident (WPH <= 4) or streams them by DMA
     constexpr bool WD = WPH >= 8;
-    if (blocks_one<4, 2, WPH, WD>(n, h, w, c_in, c_out) >= want)
-        return launch_conv_big_tile<WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
-    if (WD && blocks_one<2, 2, WPH, WD>(n, h, w, c_in, c_out) >= want)
-        return launch_one<2, 2, WPH, WD>(in, wt, n, h, w, c_in, c_out, ep, s);
-    if (blocks_one<2, 2, WPH>(n, h, w, c_in, c_out) >= want)
-        return launch_one<2, 2, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
+    if (blocks_one<4, 2, WPH, WD>(n, h, w, c_in, c_out) >= want) return 3;
+    if (WD && blocks_one<2, 2, WPH, WD>(n, h, w, c_in, c_out) >= want) return 2;
+    if (blocks_one<2, 2, WPH>(n, h, w, c_in, c_out) >= want) return 1;
+    return 0;
+}
+
+template <int WPH>
+bnn_status launch_wph(const uint32_t *in, const uint32_t *wt, int n, int h, int w, int c_in, int c_out,
+                      const EpiArgs &ep, hipStream_t s)
+{
+    constexpr bool WD = WPH >= 8;
+    switch (tile_choice_wph<WPH>(n, h, w, c_in, c_out)) {
+    case 3: return launch_conv_big_tile<WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
+    case 2: return launch_one<2, 2, WPH, WD>(in, wt, n, h, w, c_in, c_out, ep, s);
+    case 1: return launch_one<2, 2, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
+    }
     return launch_one<1, 1, WPH>(in, wt, n, h, w, c_in, c_out, ep, s);
 }
 

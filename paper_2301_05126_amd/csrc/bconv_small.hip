@@ -166,15 +166,23 @@ bnn_status launch_small(const uint32_t *in, const uint32_t *wt, const SmallGeom 
 // pixel (C_in a multiple of 64 with a power-of-two word count) and at most 1024 blocks (four per
 // compute unit; measured on the VGG-type model: faster than the tile kernels up to there, slower
 // beyond).  Returns BNN_ERR_UNSUPPORTED otherwise (the caller then takes the tile kernels).
+bool conv_binary_small_qualifies(int n, int h, int w, int c_in, int c_out)
+{
+    const int cw = (c_in + 31) / 32;
+    if ((c_in & 63) != 0 || (cw & (cw - 1)) != 0 || cw > 32) return false;
+    const TileShape ts = make_tile_shape(h, w, 32);
+    const int64_t ptiles = (int64_t)ts.tiles_x * ts.tiles_y * ((n + ts.ni - 1) / ts.ni);
+    return ptiles * ((c_out + 31) / 32) <= 1024;
+}
+
 bnn_status launch_conv_binary_small(const uint32_t *in, int n, int h, int w, int c_in, const uint32_t *wt,
                                     int c_out, const EpiArgs &ep, hipStream_t s)
 {
+    if (!conv_binary_small_qualifies(n, h, w, c_in, c_out)) return BNN_ERR_UNSUPPORTED;
     const int cw = (c_in + 31) / 32;
-    if ((c_in & 63) != 0 || (cw & (cw - 1)) != 0 || cw > 32) return BNN_ERR_UNSUPPORTED;
     const TileShape ts = make_tile_shape(h, w, 32);
     const int64_t ptiles = (int64_t)ts.tiles_x * ts.tiles_y * ((n + ts.ni - 1) / ts.ni);
     const int n_co = (c_out + 31) / 32;
-    if (ptiles * n_co > 1024) return BNN_ERR_UNSUPPORTED;
     SmallGeom g;
     g.n = n; g.h = h; g.w = w; g.cw = cw; g.c_out = c_out; g.k_bits = 9 * c_in;
     g.lth = ts.lth; g.ltw = ts.ltw; g.ni = ts.ni; g.tiles_x = ts.tiles_x; g.tiles_y = ts.tiles_y;

@@ -47,6 +47,20 @@ static bnn_status check_epilogue(const bnn_epilogue *ep, const void *raw_out, co
     return BNN_OK;
 }
 
+bnn_status check_conv_binary(const uint32_t *in_dev, int n, int h, int w, int c_in, const uint32_t *w_dev,
+                             int c_out, const bnn_epilogue *ep, int32_t *preact_out_dev,
+                             uint32_t *packed_out_dev, EpiArgs *ea)
+{
+    if (!in_dev || !w_dev) return BNN_ERR_NULL;
+    if (n < 0 || h <= 0 || w <= 0 || c_in <= 0 || c_out <= 0) return BNN_ERR_SHAPE;
+    if (c_in > (1 << 24) || (int64_t)h * w > (1 << 30)) return BNN_ERR_SHAPE;
+    const bnn_status st = check_epilogue(ep, preact_out_dev, packed_out_dev, h, w, true, ea);
+    if (st != BNN_OK) return st;
+    if (!aligned16(in_dev) || !aligned16(w_dev)) return BNN_ERR_ALIGN;
+    if (!conv_binary_supported(h, w, c_in)) return BNN_ERR_UNSUPPORTED;
+    return BNN_OK;
+}
+
 }  // namespace bnn
 
 using namespace bnn;
@@ -105,6 +119,9 @@ bnn_status bnn_fc_binary(const uint32_t *a_dev, int64_t m, int64_t k, const uint
     bnn_status st = check_epilogue(ep, c_out_dev, packed_out_dev, 1, 1, false, &ea);
     if (st != BNN_OK) return st;
     if (!aligned16(a_dev) || !aligned16(b_dev)) return BNN_ERR_ALIGN;
+    // More than 8 rows run on the matrix cores with FP32 accumulators, which hold the raw sums
+    // (at most K rounded up to a whole chunk of 2048 bits in magnitude) exactly only up to 2^24.
+    if (m > 8 && k > FC_MFMA_MAX_K) return BNN_ERR_UNSUPPORTED;
     const int64_t tiles = ceil_div64(m, 128) * ceil_div64(n, 128);
     if (tiles > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
     return launch_fc_binary(a_dev, m, k, b_dev, n, ea, (hipStream_t)stream);
@@ -114,14 +131,9 @@ bnn_status bnn_conv_binary(const uint32_t *in_dev, int n, int h, int w, int c_in
                            int c_out, const bnn_epilogue *ep, int32_t *preact_out_dev,
                            uint32_t *packed_out_dev, void *stream)
 {
-    if (!in_dev || !w_dev) return BNN_ERR_NULL;
-    if (n < 0 || h <= 0 || w <= 0 || c_in <= 0 || c_out <= 0) return BNN_ERR_SHAPE;
-    if (c_in > (1 << 24) || (int64_t)h * w > (1 << 30)) return BNN_ERR_SHAPE;
     EpiArgs ea;
-    bnn_status st = check_epilogue(ep, preact_out_dev, packed_out_dev, h, w, true, &ea);
+    const bnn_status st = check_conv_binary(in_dev, n, h, w, c_in, w_dev, c_out, ep, preact_out_dev, packed_out_dev, &ea);
     if (st != BNN_OK) return st;
-    if (!aligned16(in_dev) || !aligned16(w_dev)) return BNN_ERR_ALIGN;
-    if (!conv_binary_supported(h, w, c_in)) return BNN_ERR_UNSUPPORTED;
     return launch_conv_binary(in_dev, n, h, w, c_in, w_dev, c_out, ea, (hipStream_t)stream);
 }
 

@@ -43,8 +43,30 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
 bnn_status launch_conv_binary_small(const uint32_t *in, int n, int h, int w, int c_in,
                                     const uint32_t *wt, int c_out, const EpiArgs &ep, hipStream_t s);
 
+// The persistent tile kernels of launch_conv_binary for any supported shape (launch_conv_binary
+// itself sends small layers to the latency kernel first).
+bnn_status launch_conv_binary_tiles(const uint32_t *in, int n, int h, int w, int c_in,
+                                    const uint32_t *wt, int c_out, const EpiArgs &ep, hipStream_t s);
+
+// Argument checks of bnn_conv_binary (everything before the first HIP call); fills *ea.
+bnn_status check_conv_binary(const uint32_t *in_dev, int n, int h, int w, int c_in, const uint32_t *w_dev,
+                             int c_out, const bnn_epilogue *ep, int32_t *preact_out_dev,
+                             uint32_t *packed_out_dev, EpiArgs *ea);
+
+// Whether launch_conv_binary_small takes this layer.
+bool conv_binary_small_qualifies(int n, int h, int w, int c_in, int c_out);
+
+// Which kernel a binary convolution of this shape runs on (host-side query, launches nothing):
+// 10 = small-problem kernel, 3 = 256 x 128 block tile, 2 = 128 x 128 with streamed weights,
+// 1 = 128 x 128, 0 = 64 x 64, -1 = unsupported shape.  tiles_only: as launch_conv_binary_tiles.
+int conv_binary_kernel_choice(int n, int h, int w, int c_in, int c_out, bool tiles_only);
+
 // Whether launch_conv_binary can run this shape (LDS budget of the input patch).
 bool conv_binary_supported(int h, int w, int c_in);
+
+// Largest K of bnn_fc_binary on the matrix-core path (m > 8): K plus the zero padding to a whole
+// LDS chunk (at most 2047 bits) must not exceed 2^24, the range in which FP32 holds integers exactly.
+constexpr int64_t FC_MFMA_MAX_K = ((int64_t)1 << 24) - 2048;
 
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

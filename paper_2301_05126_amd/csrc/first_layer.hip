@@ -291,8 +291,10 @@ __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int
             const int p0 = div_magic(idx, g.mg_cin), ch = idx - p0 * g.c_in;
             const int p1 = div_magic(p0, g.mg_pw), px = p0 - p1 * pw;
             const int il = div_magic(p1, g.mg_ph), py = p1 - il * ph;
-            const int ry = py - g.pad, rx = px - g.pad;           // small: fit signed bytes
-            pk[u] = idx < total ? ((il << 16) | ((ry & 0xff) << 8) | (rx & 0xff)) : -1;
+            // 12-bit signed fields: -1024 <= -pad <= ry, rx < patch extent - pad <= 1024 (the patch has
+            // at most 1024 bytes and the interface caps pad at 1024); il < 64 keeps the sign bit clear
+            const int ry = py - g.pad, rx = px - g.pad;
+            pk[u] = idx < total ? ((il << 24) | ((ry & 0xfff) << 12) | (rx & 0xfff)) : -1;
             rel[u] = ((il * g.h + ry) * g.w + rx) * g.c_in + ch;
         }
     }
@@ -301,7 +303,7 @@ __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int
         const int8_t *origin = in + (((int64_t)img0 * g.h + y0) * g.w + x0) * g.c_in;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int y = y0 + (int)(int8_t)(pk[u] >> 8), x = x0 + (int)(int8_t)pk[u], img = img0 + (pk[u] >> 16);
+            const int y = y0 + ((pk[u] << 8) >> 20), x = x0 + ((pk[u] << 20) >> 20), img = img0 + (pk[u] >> 24);
             const bool in_patch = pk[u] >= 0;
             const bool inside = in_patch & (img < g.n) & ((unsigned)y < (unsigned)g.h) & ((unsigned)x < (unsigned)g.w);
             const int8_t b = inside ? origin[rel[u]] : in[0];
@@ -482,15 +484,15 @@ __global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ 
     const int n0 = (blockIdx.x % nbn) * 64 + (wave & 1) * 32;
     const int64_t arow = (m0 + l32 < M) ? m0 + l32 : M - 1;
     const int brow = (n0 + l32 < N) ? n0 + l32 : N - 1;
-    const int8_t *ap = A + arow * K + half * 16;
-    const int8_t *bp = Wt + (int64_t)brow * K + half * 16;
+    const int8_t *ap = A + arow * K;
+    const int8_t *bp = Wt + (int64_t)brow * K;
     v16i acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0;
     const int nsteps = (K + 31) / 32;
     for (int ks = 0; ks < nsteps; ++ks) {
         const bool ok = ks * 32 + half * 16 < K;         // K % 16 == 0: a 16-byte slice is all in or all out
-        const int koff = ok ? ks * 32 : 0;
+        const int koff = ok ? ks * 32 + half * 16 : 0;   // a slice past K re-reads the row's first one (in bounds)
         v4i a = *reinterpret_cast<const v4i *>(ap + koff);
         v4i b = *reinterpret_cast<const v4i *>(bp + koff);
         if (!ok) { a = v4i{0, 0, 0, 0}; b = v4i{0, 0, 0, 0}; }
@@ -524,7 +526,8 @@ template <int NG>
 bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, const EpiArgs &ep, hipStream_t s)
 {
     g.n_co_tiles = (g.c_out + 64 * NG - 1) / (64 * NG);
-    const bool pipe = g.patch_bytes <= 1024;
+    // pipelined patch: four bytes per thread, each addressed by a 32-bit offset from the tile origin
+    const bool pipe = g.patch_bytes <= 1024 && (int64_t)(g.ni + 1) * g.h * g.w * g.c_in < 0x7fffffffLL;
     const size_t smem = (size_t)64 * NG * (g.kp + 16) + 2 * 256 * 2 * NG * 4 + 64 * NG * 4 +
                         (size_t)(pipe ? 2 : 1) * g.patch_bytes;
     const int64_t items = (int64_t)g.tiles_x * g.tiles_y * ((g.n + g.ni - 1) / g.ni);

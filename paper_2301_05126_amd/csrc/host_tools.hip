@@ -1,7 +1,11 @@
 // Host-only helpers of libbnn: the layer-to-implementation mapping of the paper's Alg. 1 over
 // a profiled latency table, and batch-norm folding into (threshold, flip).  No GPU code.
+#include <algorithm>
 #include <cmath>
+#include <functional>
 #include <limits>
+#include <new>
+#include <vector>
 
 #include "bnn_internal.h"
 
@@ -12,38 +16,36 @@ bnn_status bnn_map_layers(const double *cpu_us, const double *gpu_us, int n_batc
 {
     if (!cpu_us || !gpu_us || !best_batch || !mapping) return BNN_ERR_NULL;
     if (n_batch < 1 || n_layers < 1 || n_impl < 1) return BNN_ERR_SHAPE;
-    const int64_t count = (int64_t)n_batch * n_layers * n_impl;
-    for (int64_t i = 0; i < count; ++i) {
+    const size_t cells = (size_t)n_batch * n_layers;
+    for (size_t i = 0; i < cells * n_impl; ++i) {
         if (!std::isfinite(cpu_us[i]) || !std::isfinite(gpu_us[i]) || cpu_us[i] < 0 || gpu_us[i] < 0)
             return BNN_ERR_SHAPE;
     }
-    double result_time = std::numeric_limits<double>::infinity();
-    int proper = 0;
-    for (int b = 0; b < n_batch; ++b) {
-        double sum_min = 0.0;
-        for (int l = 0; l < n_layers; ++l) {
-            double min_time = std::numeric_limits<double>::infinity();
-            for (int j = 0; j < n_impl; ++j) {
-                const int64_t at = ((int64_t)b * n_layers + l) * n_impl + j;
-                const double t = cpu_us[at] + gpu_us[at];
-                if (t < min_time) min_time = t;
-            }
-            sum_min += min_time;
-        }
-        if (sum_min < result_time) { result_time = sum_min; proper = b; }
+    // The search of Alg. 1 separates: the cheapest implementation of a (batch size, layer) cell
+    // does not depend on any other cell, and a batch size's cost is the sum over its row of cells.
+    // So: one argmin per cell into a table, one sum per row, the cheapest row, and that row of the
+    // table is the answer.  std::min_element returns the first of equal minima, which is the
+    // tie rule of a strict "smaller than" scan.
+    std::vector<int> choice;
+    std::vector<double> row_cost, latency;
+    try {
+        choice.resize(cells);
+        row_cost.assign(n_batch, 0.0);
+        latency.resize(n_impl);
+    } catch (const std::bad_alloc &) {
+        return BNN_ERR_UNSUPPORTED;      // no exception crosses the C boundary
     }
-    for (int l = 0; l < n_layers; ++l) {
-        double min_time = std::numeric_limits<double>::infinity();
-        int pick = 0;
-        for (int j = 0; j < n_impl; ++j) {
-            const int64_t at = ((int64_t)proper * n_layers + l) * n_impl + j;
-            const double t = cpu_us[at] + gpu_us[at];
-            if (t < min_time) { min_time = t; pick = j; }
-        }
-        mapping[l] = pick;
+    for (size_t cell = 0; cell < cells; ++cell) {
+        const double *c = cpu_us + cell * n_impl, *g = gpu_us + cell * n_impl;
+        std::transform(c, c + n_impl, g, latency.begin(), std::plus<double>());
+        const auto cheapest = std::min_element(latency.begin(), latency.end());
+        choice[cell] = (int)(cheapest - latency.begin());
+        row_cost[cell / n_layers] += *cheapest;
     }
-    *best_batch = proper;
-    if (total_us) *total_us = result_time;
+    const int winner = (int)(std::min_element(row_cost.begin(), row_cost.end()) - row_cost.begin());
+    std::copy_n(choice.begin() + (size_t)winner * n_layers, n_layers, mapping);
+    *best_batch = winner;
+    if (total_us) *total_us = row_cost[winner];
     return BNN_OK;
 }
 

@@ -28,27 +28,34 @@ __device__ __forceinline__ v4i make_raw_rsrc(const void *base, unsigned bytes)
 // Written as inline assembly so that the compiler does not serialise the transfer against
 // the LDS reads of the tile being multiplied; completion is awaited explicitly
 // (s_waitcnt vmcnt(0)) before the barrier that publishes the buffer.  lds_base is wave-uniform.
+// Each statement overwrites M0 and says so in its clobber list, so the compiler's own uses of M0
+// are re-initialised after it (it warns that M0 is a reserved register; that warning is silenced
+// for these four statements only).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lds_dma16(v4i rsrc, unsigned lds_base, unsigned voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory", "m0");
 }
 // the same with a scalar byte offset added to the address
 __device__ __forceinline__ void lds_dma16_soff(v4i rsrc, unsigned lds_base, unsigned voff, unsigned soff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 __device__ __forceinline__ void lds_dma4_soff(v4i rsrc, unsigned lds_base, unsigned voff, unsigned soff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 __device__ __forceinline__ void lds_dma4(v4i rsrc, unsigned lds_base, unsigned voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory", "m0");
 }
+
+#pragma clang diagnostic pop
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 

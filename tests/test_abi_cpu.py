@@ -73,6 +73,9 @@ def test_fc_validation(lib):
     assert f(P16, 4, 64, P16, 8, C.byref(bad_pool), None, P16, None) == SHAPE
     no_thr = lib.Epilogue(None, None, 1, 0)
     assert f(P16, 4, 64, P16, 8, C.byref(no_thr), None, P16, None) == NULL
+    # more than 8 rows run with FP32 accumulators: K beyond their exact range is refused
+    assert f(P16, 9, (1 << 24) - 2047, P16, 8, None, P16, None, None) == UNSUP
+    assert f(P16, 9, (1 << 30) + 1, P16, 8, None, P16, None, None) == SHAPE
 
 
 def test_conv_validation(lib):
@@ -161,3 +164,38 @@ def test_model_create_validation_and_workspace(lib):
     with pytest.raises(lib.BnnError) as e:
         lib.bnn_model_create(bad, 4, 32, 32, 3)
     assert e.value.status == UNSUP
+
+
+def test_product_has_no_environment_switches():
+    # dispatch depends on shapes only: the library reads no environment variable
+    import subprocess
+    so = os.path.join(ROOT, "paper_2301_05126_amd", "libbnn.so")
+    syms = subprocess.run(["nm", "-D", "--undefined-only", so], capture_output=True, text=True).stdout
+    assert "getenv" not in syms
+
+
+def test_test_hook_library_is_separate(lib):
+    # the hook that reaches the tile kernels with small shapes lives in its own library
+    assert not hasattr(lib.api._lib, "bnn_test_conv_binary_tiles")
+    hook = os.path.join(ROOT, "tests", "hooks", "libbnn_test_hooks.so")
+    if os.path.exists(hook):
+        assert hasattr(C.CDLL(hook), "bnn_test_conv_binary_tiles")
+
+
+def test_kernel_choice_of_the_benchmark_shapes(lib):
+    # host-side query (no GPU work): the shapes of the parity tests that are meant to reach the
+    # 256 x 128 block tile do reach it, and so do the layers bench.py times
+    from tests.gpu_util import KERNEL_SMALL, TILE_256x128, TILE_64x64, conv_kernel_choice
+    import workloads as W
+    from tests.test_gpu_bigtile import BIG_TILE_SHAPES
+    for n, hw, ci, co in BIG_TILE_SHAPES:
+        assert conv_kernel_choice(n, hw, hw, ci, co) == TILE_256x128, (n, hw, ci, co)
+    _, layers, _ = W.model_by_name("vgg_small")
+    for L in layers:
+        if L.kind == "conv_binary":
+            assert conv_kernel_choice(4096, L.h_in, L.w_in, L.c_in, L.c_out) == TILE_256x128
+            assert conv_kernel_choice(1, L.h_in, L.w_in, L.c_in, L.c_out) == KERNEL_SMALL
+            assert conv_kernel_choice(1, L.h_in, L.w_in, L.c_in, L.c_out, tiles_only=True) == TILE_64x64
+    for hw, c in W.CONV_SWEEP_SHAPES:
+        assert conv_kernel_choice(1024, hw, hw, c, c) in (TILE_256x128, 1, 2)
+    assert conv_kernel_choice(4, 8, 8, 2048, 32) == -1       # more than 1024 channels: unsupported

@@ -7,8 +7,8 @@ import torch
 import oracle
 import paper_2301_05126_amd as P
 import workloads as W
-from tests.gpu_util import (DEV, DeviceModel, dev, empty_i32, fill_i32, host_u32, pack_on_gpu,
-                            require_gpu)
+from tests.gpu_util import (DEV, DeviceModel, conv_binary_tiles, dev, empty_i32, fill_i32, host_u32,
+                            pack_on_gpu, require_gpu)
 from tests.helpers import pack_pm1
 
 pytestmark = pytest.mark.gpu
@@ -147,19 +147,17 @@ def conv_weights_packed(wt):
 
 @pytest.mark.parametrize("path", ["auto", "tiles"])
 @pytest.mark.parametrize("n,h,w,ci,co,pool", CONV_SHAPES)
-def test_conv_binary_raw_and_fused(n, h, w, ci, co, pool, path, monkeypatch):
-    # "tiles": the tile kernels also for shapes that would take the small-problem kernel
-    if path == "tiles":
-        monkeypatch.setenv("BNN_CONV_TILES_ONLY", "1")
-    else:
-        monkeypatch.delenv("BNN_CONV_TILES_ONLY", raising=False)
+def test_conv_binary_raw_and_fused(n, h, w, ci, co, pool, path):
+    # "auto": bnn_conv_binary as the library dispatches it; "tiles": the persistent tile kernels
+    # also for shapes that the library would send to its small-problem kernel (test hook)
+    conv = P.bnn_conv_binary if path == "auto" else conv_binary_tiles
     print("conv", path, n, h, w, ci, co, pool, flush=True)
     rng = rng_of(n + h * 3 + w * 5 + ci * 7 + co * 11)
     x, wt = pm1(rng, (n, h, w, ci)), pm1(rng, (co, 3, 3, ci))
     want = oracle.conv2d(x, wt, 1, -1)
     xd, wd = dev(pack_pm1(x)), dev(conv_weights_packed(wt))
     raw = fill_i32((n, h, w, co), 99999)
-    P.bnn_conv_binary(xd, n, h, w, ci, wd, co, preact_out=raw)
+    conv(xd, n, h, w, ci, wd, co, preact_out=raw)
     np.testing.assert_array_equal(raw.cpu().numpy(), want)
     k = 9 * ci
     thr = rng.integers(-(k // 8), k // 8 + 1, size=co).astype(np.int32)
@@ -171,17 +169,15 @@ def test_conv_binary_raw_and_fused(n, h, w, ci, co, pool, path, monkeypatch):
         s = oracle.maxpool2(s)
     raw2 = fill_i32((n, h, w, co), 99999)
     packed = fill_i32((n, h // pool, w // pool, (co + 31) // 32), -1)
-    P.bnn_conv_binary(xd, n, h, w, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=pool,
-                      preact_out=raw2, packed_out=packed)
+    conv(xd, n, h, w, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=pool, preact_out=raw2, packed_out=packed)
     np.testing.assert_array_equal(raw2.cpu().numpy(), want)
     np.testing.assert_array_equal(host_u32(packed), pack_pm1(s))
     packed2 = fill_i32((n, h // pool, w // pool, (co + 31) // 32), -1)
-    P.bnn_conv_binary(xd, n, h, w, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=pool, packed_out=packed2)
+    conv(xd, n, h, w, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=pool, packed_out=packed2)
     np.testing.assert_array_equal(host_u32(packed2), pack_pm1(s))
     if pool == 2:
         packed3 = fill_i32((n, h // 2, w // 2, (co + 31) // 32), -1)
-        P.bnn_conv_binary(xd, n, h, w, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=2, pool_first=1,
-                          packed_out=packed3)
+        conv(xd, n, h, w, ci, wd, co, thr=dev(thr), flip=dev(flip), pool=2, pool_first=1, packed_out=packed3)
         np.testing.assert_array_equal(host_u32(packed3),
                                       pack_pm1(oracle.step(oracle.maxpool2(want), thr, flip)))
 
@@ -215,7 +211,12 @@ FIRST_SHAPES = [(2, 28, 28, 1, 64, 3, 3, 1, -1, 2), (2, 32, 32, 3, 128, 3, 3, 1,
                 # one K step (two kernel rows), two channel groups; four full kernel rows with a ragged
                 # second channel tile; kernel rows wider than 16 bytes with a patch beyond 1 KB
                 (2, 9, 9, 2, 96, 2, 2, 0, -1, 1), (1, 16, 16, 4, 130, 4, 4, 1, -1, 1),
-                (2, 12, 12, 8, 64, 3, 3, 1, 3, 2)]
+                (2, 12, 12, 8, 64, 3, 3, 1, 3, 2),
+                # padding wider than a signed byte (tile-relative coordinates down to -200 / -130)
+                (1, 300, 4, 1, 8, 3, 3, 200, -1, 2), (1, 6, 6, 2, 16, 3, 3, 130, 3, 1),
+                # 1x1 layer with exactly one 16-byte slice per row (K = 16), last row included
+                (3, 1, 1, 16, 40, 1, 1, 0, -1, 1), (70, 1, 1, 16, 64, 1, 1, 0, -1, 1),
+                (5, 1, 1, 48, 33, 1, 1, 0, -1, 1)]
 
 
 @pytest.mark.parametrize("n,h,w,ci,co,kh,kw,pad,padv,pool", FIRST_SHAPES)
@@ -282,7 +283,9 @@ def check_model(name, batch, modes):
 
 
 @pytest.mark.parametrize("name,batch", [("mlp", 64), ("small_cnn", 1), ("small_cnn", 5), ("small_cnn", 256),
-                                        ("vgg_small", 1), ("vgg_small", 3), ("vgg_small", 32)])
+                                        ("vgg_small", 1), ("vgg_small", 3), ("vgg_small", 32),
+                                        # batch 64: the first layer takes two channel groups per block
+                                        ("vgg_small", 64)])
 def test_run_model_layer_by_layer(name, batch):
     check_model(name, batch, [P.RUN_TIMED, P.RUN_STREAM])
 

@@ -295,6 +295,83 @@ def test_model_layer_chain_matches_manual_composition():
     np.testing.assert_array_equal(logits, x3)
 
 
+def _np_step(x, thr, flip):
+    return np.where((x > thr.astype(np.int64)) ^ (flip == 1), 1, -1).astype(np.int64)
+
+
+def _np_pool(x):
+    n, h, w, c = x.shape
+    return x.reshape(n, h // 2, 2, w // 2, 2, c).max(axis=(2, 4))
+
+
+@pytest.mark.parametrize("pool_first", [False, True])
+@pytest.mark.parametrize("first_pad_value", [-1, 5])
+def test_small_cnn_matches_numpy_composition(pool_first, first_pad_value):
+    # The Python composition in oracle.run_layer / run_model (which layer gets which pad value,
+    # step and pool in which order, flatten, no step on the logits layer) against a chain written
+    # out here with numpy only: explicit padding + einsum, np.where, reshape-max.
+    import workloads as W
+    cid, layers, (ih, iw, ic) = W.model_by_name("small_cnn")
+    imgs = W.draw_images(W.rng_for(cid, 0, 0), 2, ih, iw, ic)
+    logits, trace = oracle.run_model(layers, imgs, first_pad_value=first_pad_value, pool_first=pool_first)
+
+    def hidden(x, L):
+        if pool_first:
+            return _np_step(_np_pool(x), L.thr, L.flip)
+        return _np_pool(_np_step(x, L.thr, L.flip))
+
+    c1, c2, f1, f2 = layers
+    x1 = _np_conv(imgs, c1.weights, 1, first_pad_value)            # int8 pixels, pad value as given
+    a1 = hidden(x1, c1)
+    x2 = _np_conv(a1, c2.weights, 1, -1)                           # binary layer: padding is -1
+    a2 = hidden(x2, c2)
+    x3 = a2.reshape(2, 7 * 7 * 64) @ f1.weights.astype(np.int64).T   # flatten (h, w, c), c fastest
+    a3 = _np_step(x3, f1.thr, f1.flip)
+    x4 = a3 @ f2.weights.astype(np.int64).T                        # logits: no step
+    np.testing.assert_array_equal(trace[0][0], x1)
+    np.testing.assert_array_equal(trace[0][1], a1)
+    np.testing.assert_array_equal(trace[1][0], x2)
+    np.testing.assert_array_equal(trace[1][1], a2)
+    np.testing.assert_array_equal(trace[2][0], x3)
+    np.testing.assert_array_equal(trace[2][1].reshape(2, 2048), a3)
+    np.testing.assert_array_equal(logits, x4)
+    assert trace[3][1] is None
+    # the planted alternatives really differ on this input, so the equalities above pin them
+    assert not np.array_equal(_np_conv(a1, c2.weights, 1, 0), x2)              # pad 0 instead of -1
+    assert not np.array_equal(_np_step(_np_pool(x1), c1.thr, c1.flip),
+                              _np_pool(_np_step(x1, c1.thr, c1.flip)))         # the two pool orders
+
+
+def test_conv_chain_with_and_without_pool_matches_numpy():
+    # a VGG-like fragment (binary conv without pool -> binary conv with pool -> FC) through
+    # oracle.run_layer, per layer, in both pool orders
+    import workloads as W
+    rng = np.random.default_rng(2024)
+    la = W.Layer("conv_binary", 6, 40, 3, 3, 1, pool=1)
+    lb = W.Layer("conv_binary", 40, 8, 3, 3, 1, pool=2)
+    lc = W.Layer("fc_binary", 3 * 2 * 8, 5, step=False)
+    for L, k in ((la, 54), (lb, 360)):
+        L.weights = pm1((L.c_out, 3, 3, L.c_in), rng)
+        L.thr = rng.integers(-k // 8, k // 8 + 1, size=L.c_out).astype(np.int32)
+        L.flip = rng.integers(0, 2, size=L.c_out).astype(np.uint8)
+    lc.weights = pm1((5, 48), rng)
+    act = pm1((3, 6, 4, 6), rng)
+    for pool_first in (False, True):
+        pre_a, out_a = oracle.run_layer(la, act, pool_first=pool_first)
+        xa = _np_conv(act, la.weights, 1, -1)
+        sa = _np_step(xa, la.thr, la.flip)
+        np.testing.assert_array_equal(pre_a, xa)
+        np.testing.assert_array_equal(out_a, sa)                   # no pool: order flag is irrelevant
+        pre_b, out_b = oracle.run_layer(lb, out_a, pool_first=pool_first)
+        xb = _np_conv(sa, lb.weights, 1, -1)
+        sb = _np_step(_np_pool(xb), lb.thr, lb.flip) if pool_first else _np_pool(_np_step(xb, lb.thr, lb.flip))
+        np.testing.assert_array_equal(pre_b, xb)
+        np.testing.assert_array_equal(out_b, sb)
+        pre_c, out_c = oracle.run_layer(lc, out_b, pool_first=pool_first)
+        np.testing.assert_array_equal(pre_c, sb.reshape(3, 48) @ lc.weights.astype(np.int64).T)
+        assert out_c is None
+
+
 def test_helper_packer_roundtrip():
     from tests.helpers import unpack_words
     a = pm1((3, 5, 70))
