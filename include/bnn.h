@@ -251,6 +251,28 @@ bnn_status bnn_run_model(bnn_model *m, const int8_t *input_dev, int32_t *logits_
                          bnn_layer_timing *timings, bnn_host_layer_fn host_fn, void *host_ctx,
                          void *stream);
 
+/*
+ * bnn_run_model for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same model, same kernels and same results as bnn_run_model in BNN_RUN_STREAM mode (plain
+ * asynchronous launches on `stream`, taps honoured), but the two ping-pong activation buffers
+ * live in a fixed array of BNN_NOALLOC_SCRATCH_BYTES bytes of device memory inside the
+ * library (each GPU the library runs on holds one from load time until the process ends).
+ * The call allocates and frees nothing, on the host side of HIP or through any library.  Its
+ * first call on a device looks the array's address up (one hipGetSymbolAddress, no stream
+ * work); make that call outside any capture.
+ *   - a model whose bnn_model_workspace_bytes() exceeds BNN_NOALLOC_SCRATCH_BYTES is refused
+ *     with BNN_ERR_WORKSPACE before any HIP call (VGG-small fits up to batch 512);
+ *   - all calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ *     (two streams, two threads) race and give undefined activations; order them;
+ *   - the array keeps the previous call's contents; no call depends on them (every layer
+ *     overwrites its whole output before it is read).
+ * Errors: NULL, ALIGN, WORKSPACE, UNSUPPORTED (device ordinal >= 64), HIP.
+ */
+#define BNN_NOALLOC_SCRATCH_BYTES (16u << 20)
+bnn_status bnn_run_model_noalloc(bnn_model *m, const int8_t *input_dev, int32_t *logits_dev,
+                                 void *stream);
+
 /* Free the host object (and its captured graph).  NULL is allowed. */
 void bnn_model_destroy(bnn_model *m);
 

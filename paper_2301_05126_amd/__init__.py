@@ -12,7 +12,7 @@ from . import runtime  # noqa: F401
 from .api import (  # noqa: F401
     BnnError, Epilogue, LayerDesc, LayerTiming, Model,
     bnn_pack_bits, bnn_conv_first_int8, bnn_conv_binary, bnn_fc_binary,
-    bnn_threshold_sign_maxpool, bnn_model_create, bnn_run_model, bnn_model_destroy,
+    bnn_threshold_sign_maxpool, bnn_model_create, bnn_run_model, bnn_run_model_noalloc, bnn_model_destroy,
     bnn_model_workspace_bytes, bnn_status_string, bnn_last_hip_error, bnn_version,
     bnn_map_layers, bnn_fold_batchnorm,
     RUN_TIMED, RUN_GRAPH, RUN_STREAM, LAYER_CONV_FIRST_INT8, LAYER_CONV_BINARY, LAYER_FC_BINARY,

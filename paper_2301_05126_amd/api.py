@@ -57,6 +57,9 @@ _lib.bnn_model_num_layers.argtypes = [_vp]
 _lib.bnn_model_num_classes.argtypes = [_vp]
 _lib.bnn_run_model.argtypes = [_vp, _vp, _vp, _vp, C.c_size_t, _i, C.POINTER(LayerTiming),
                                HOST_LAYER_FN, _vp, _vp]
+_lib.bnn_run_model_noalloc.argtypes = [_vp, _vp, _vp, _vp]
+_lib.bnn_run_model_noalloc.restype = _i
+NOALLOC_SCRATCH_BYTES = 16 << 20
 _lib.bnn_model_destroy.argtypes = [_vp]
 _lib.bnn_model_destroy.restype = None
 _dp = C.POINTER(C.c_double)
@@ -184,6 +187,11 @@ def bnn_run_model(model, input_dev, logits_dev, workspace_dev, workspace_bytes, 
                               workspace_bytes, mode, timings, cb, None, _stream(stream)),
            "bnn_run_model")
     return list(timings) if timings is not None else None
+
+
+def bnn_run_model_noalloc(model, input_dev, logits_dev, stream=None):
+    _check(_lib.bnn_run_model_noalloc(model.handle, _ptr(input_dev), _ptr(logits_dev), _stream(stream)),
+           "bnn_run_model_noalloc")
 
 
 def bnn_model_destroy(model):

@@ -1,6 +1,7 @@
 // C ABI of libbnn: host-side validation, dispatch to the kernel launchers, and the
 // whole-model runner with per-layer timing and hipGraph replay.
 #include <chrono>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -175,6 +176,44 @@ struct bnn_model {
 };
 
 static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- device scratch of bnn_run_model_noalloc: the two ping-pong activation buffers that
+// bnn_run_model takes from its caller's workspace, here in a fixed array that every GPU the
+// library runs on holds from the moment the library is loaded until the process ends.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[BNN_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+// In host code the array's name is only a handle for the symbol lookup below, never an address:
+// each device holds its own copy at its own address, fetched once per device (with that device
+// current) and used from then on for everything the host does with the array's memory.
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[MAX_DEVICES] = {};
+
+bnn_status static_scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    bnn_status st = bnn::hip_result(hipGetDevice(&dev));
+    if (st != BNN_OK) return st;
+    if (dev < 0 || dev >= MAX_DEVICES) return BNN_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        st = bnn::hip_result(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (st != BNN_OK) return st;
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u) != 0) return BNN_ERR_ALIGN;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return BNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
 
 bnn_status bnn_model_create(const bnn_layer_desc *layers, int n_layers, int batch, int in_h, int in_w,
                             int in_c, bnn_model **out)
@@ -417,6 +456,19 @@ bnn_status bnn_run_model(bnn_model *m, const int8_t *input_dev, int32_t *logits_
         }
     }
     return BNN_OK;
+}
+
+bnn_status bnn_run_model_noalloc(bnn_model *m, const int8_t *input_dev, int32_t *logits_dev, void *stream)
+{
+    if (!m || !input_dev || !logits_dev) return BNN_ERR_NULL;
+    if (!aligned16(input_dev) || !aligned16(logits_dev)) return BNN_ERR_ALIGN;
+    if (2 * m->buf_bytes > (size_t)BNN_NOALLOC_SCRATCH_BYTES) return BNN_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const bnn_status st = static_scratch_of_current_device(&ws);
+    if (st != BNN_OK) return st;
+    // every layer overwrites the whole of its output buffer before the next layer reads it, so
+    // nothing in the array has to start at zero, whatever an earlier call left there
+    return enqueue_chain(m, input_dev, logits_dev, ws, true, (hipStream_t)stream, false);
 }
 
 void bnn_model_destroy(bnn_model *m)

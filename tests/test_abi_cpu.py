@@ -199,3 +199,27 @@ def test_kernel_choice_of_the_benchmark_shapes(lib):
     for hw, c in W.CONV_SWEEP_SHAPES:
         assert conv_kernel_choice(1024, hw, hw, c, c) in (TILE_256x128, 1, 2)
     assert conv_kernel_choice(4, 8, 8, 2048, 32) == -1       # more than 1024 channels: unsupported
+
+
+def test_run_model_noalloc_validation(lib):
+    # the entry point without a workspace argument refuses, on the host and before any HIP call,
+    # what does not fit its fixed device array
+    f = lib.api._lib.bnn_run_model_noalloc
+
+    def vgg(batch):
+        mk = lambda kind, ci, co, pool=1, step=1: lib.LayerDesc(kind, ci, co, 3, 3, 1, -1, step, pool, 0,
+                                                                P16, P16 if step else None, None, None, None)
+        descs = [mk(0, 3, 128), mk(1, 128, 128, 2), mk(1, 128, 256), mk(1, 256, 256, 2), mk(1, 256, 512),
+                 mk(1, 512, 512, 2), mk(2, 8192, 1024), mk(2, 1024, 1024), mk(2, 1024, 10, 1, 0)]
+        return lib.bnn_model_create(descs, batch, 32, 32, 3)
+
+    small, big = vgg(512), vgg(513)
+    assert lib.bnn_model_workspace_bytes(small) == lib.api.NOALLOC_SCRATCH_BYTES
+    assert lib.bnn_model_workspace_bytes(big) > lib.api.NOALLOC_SCRATCH_BYTES
+    assert f(big.handle, P16, P16, None) == WS
+    assert f(None, P16, P16, None) == NULL
+    assert f(small.handle, None, P16, None) == NULL
+    assert f(small.handle, P16, None, None) == NULL
+    assert f(small.handle, P8, P16, None) == ALIGN
+    text = open(os.path.join(ROOT, "include", "bnn.h")).read()
+    assert "#define BNN_NOALLOC_SCRATCH_BYTES (16u << 20)" in text
