@@ -29,6 +29,13 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // launches are latency-bound), the 256 x 256 tile short ones (registers).
 constexpr int chunk_words(int tm, int tn) { return tm * tn >= 16 ? 16 : (tm * tn >= 4 ? 32 : 64); }
 
+// (experiments may override the start stagger at build time)
+#ifdef BNN_GEMM_TUNE
+static unsigned gemm_stagger_ticks(unsigned dflt) { const char *e = getenv("GEMM_STAGGER_US"); return e ? (unsigned)(atof(e) * 100) : dflt; }
+#else
+static unsigned gemm_stagger_ticks(unsigned dflt) { return dflt; }
+#endif
+
 template <int VEC>
 __device__ __forceinline__ uint4 load_row_words(const uint32_t *__restrict__ base, int64_t row,
                                                 int64_t rows, int kw_total, int kpos)
@@ -70,10 +77,19 @@ __device__ __forceinline__ uint32_t word_of(const uint4 &v, int q)
     return q == 0 ? v.x : (q == 1 ? v.y : (q == 2 ? v.z : v.w));
 }
 
+// Where a block's tile lies and when the block starts.
+struct GemmWalk {
+    int nbm, nbn;            // tiles along M and N
+    unsigned stagger_ticks;  // start delays of the first 256 blocks are spread over this many 100 MHz ticks
+};
+
+// One block per tile.  Tile numbers run column-major inside bands of eight tile rows, and the
+// blocks that hardware deals to one XCD (ids equal modulo 8) take neighbouring numbers, so the
+// tiles in flight on one L2 form a patch that shares rows of A and of B.
 template <int TM, int TN, int VEC>
 __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict__ A,
                                                       const uint32_t *__restrict__ B, int64_t M, int64_t N,
-                                                      int Kw, int K, int nbn, EpiArgs ep)
+                                                      int Kw, int K, GemmWalk gw, EpiArgs ep)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;     // 2 x 2 waves
     constexpr int KC = chunk_words(TM, TN);
@@ -88,20 +104,19 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
     const int lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
-    // XCD-aware order (consecutive block ids go round-robin to the 8 XCDs / L2s): renumber so
-    // that the blocks walking one row block of A share an L2.
-    unsigned bid = blockIdx.x;
-    if ((gridDim.x & 7) == 0) bid = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int64_t m0 = (int64_t)(bid / nbn) * BM;
-    const int64_t n0 = (int64_t)(bid % nbn) * BN;
 
-    v16f acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const int nblk = (int)gridDim.x;
+    int tile = (int)blockIdx.x;
+    if ((nblk & 7) == 0) tile = (int)(blockIdx.x & 7) * (nblk >> 3) + (int)(blockIdx.x >> 3);
+    int64_t m0, n0;
+    {
+        const int band = tile / (8 * gw.nbn);
+        const int rows_in_band = min(8, gw.nbm - band * 8);
+        const int idx = tile - band * 8 * gw.nbn;
+        const int nb = idx / rows_in_band;
+        m0 = (int64_t)(band * 8 + (idx - nb * rows_in_band)) * BM;
+        n0 = (int64_t)nb * BN;
+    }
 
     // staging: a chunk of a tile is (rows x UPR) 16-byte units; SA units of A, SB of B per thread
     uint4 pa[SA], pb[SB];
@@ -119,6 +134,17 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
     };
     prefetch(0);
 
+    // Several rounds of 256 x 256 tiles (one block per compute unit at a time): the first round's
+    // blocks start spread over a few microseconds.  Every later block starts when a compute unit
+    // falls free, so tiles keep ending at different times on different compute units for the whole
+    // run, and the tiles' stores (256 KB each) do not all meet in the memory system at once.
+    // (Bounded wait on the free-running 100 MHz counter.)
+    if (gw.stagger_ticks && blockIdx.x < 256u) {
+        const unsigned long long wait = (unsigned long long)blockIdx.x * gw.stagger_ticks / 256u;
+        const long long t0 = wall_clock64();
+        while ((unsigned long long)(wall_clock64() - t0) < wait) __builtin_amdgcn_s_sleep(16);
+    }
+
     // VALU instructions to place behind each MFMA: 7 per expanded word, (TM+TN) words per step
     constexpr int VPM = (7 * (TM + TN) + TM * TN - 1) / (TM * TN);
     uint32_t sgn = 0x88888888u, one = 0x22222222u;
@@ -126,122 +152,154 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
     asm volatile("" : "+v"(one));
 
     const int nchunks = (Kw + KC - 1) / KC;
+    const int corr = nchunks * KC * 32 - K;      // padded positions all counted as +1
     const uint32_t *a_rd = As + (wm * TM * 32 + l32) * LS + half * 4;
     const uint32_t *b_rd = Bs + (wn * TN * 32 + l32) * LS + half * 4;
-    for (int kc = 0; kc < nchunks; ++kc) {
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < SA; ++r) {
-            const int idx = t + 256 * r;
-            *reinterpret_cast<uint4 *>(As + (idx / UPR) * LS + (idx % UPR) * 4) = pa[r];
-        }
-#pragma unroll
-        for (int r = 0; r < SB; ++r) {
-            const int idx = t + 256 * r;
-            *reinterpret_cast<uint4 *>(Bs + (idx / UPR) * LS + (idx % UPR) * 4) = pb[r];
-        }
-        __syncthreads();
-        if (kc + 1 < nchunks) prefetch((kc + 1) * KC);
 
-        // a chunk = NG groups of 8 words; lane half h owns words [8g + 4h, 8g + 4h + 4).
-        // Operands of step s+1 are expanded on the VALU while the matrix core runs step s.
-        uint4 wa[NG][TM], wb[NG][TN];
-#pragma unroll
-        for (int g = 0; g < NG; ++g) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) wa[g][i] = *reinterpret_cast<const uint4 *>(a_rd + i * 32 * LS + g * 8);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) wb[g][j] = *reinterpret_cast<const uint4 *>(b_rd + j * 32 * LS + g * 8);
-        }
-        v8i a[2][TM], b[2][TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a[0][i] = expand_fp4(wa[0][i].x, sgn, one);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[0][j] = expand_fp4(wb[0][j].x, sgn, one);
-#pragma unroll
-        for (int st = 0; st < NST; ++st) {
-            const int cur = st & 1, nxt = cur ^ 1;
-            if (st + 1 < NST) {
-                const int g = (st + 1) >> 2, q = (st + 1) & 3;
-#pragma unroll
-                for (int i = 0; i < TM; ++i) a[nxt][i] = expand_fp4(word_of(wa[g][i], q), sgn, one);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) b[nxt][j] = expand_fp4(word_of(wb[g][j], q), sgn, one);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        a[cur][i], b[cur][j], acc[i][j], 4, 4, 0, 0, 0, 0);
-            // interleave: one MFMA, then its share of the next step's VALU work
-#pragma unroll
-            for (int k = 0; k < TM * TN; ++k) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
-            }
-        }
-    }
-
-    // ---- epilogue.  Accumulator register r of lane (l32, half) in tile (i, j) is
-    // row 32i + 8(r/4) + 4*half + r%4, column 32j + l32.
-    const int corr = nchunks * KC * 32 - K;      // padded positions all counted as +1
-    const int64_t rbase = m0 + wm * TM * 32 + half * 4;
-    const int64_t cbase = n0 + wn * TN * 32 + l32;
-    if (ep.preact) {
+    {
+        v16f acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int64_t col = cbase + j * 32;
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t row = rbase + i * 32 + (r >> 2) * 8 + (r & 3);
-                    if (row < M && col < N) ep.preact[row * N + col] = (int)acc[i][j][r] - corr;
-                }
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        for (int kc = 0; kc < nchunks; ++kc) {
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < SA; ++r) {
+                const int idx = t + 256 * r;
+                *reinterpret_cast<uint4 *>(As + (idx / UPR) * LS + (idx % UPR) * 4) = pa[r];
             }
-    }
-    if (ep.packed) {
-        // A ballot over the 32 columns of a tile is the packed word of one row (one per lane
-        // half).  Lane r of each half keeps the word of register r, so that a tile's 32 words
-        // leave with one store instruction per row block instead of one per word.
-        const int64_t nw = (N + 31) >> 5;
-        int thr[TN];
-        bool flip[TN], cok[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int64_t col = cbase + j * 32;
-            cok[j] = col < N;
-            thr[j] = cok[j] ? ep.thr[col] : 0;
-            flip[j] = cok[j] && ep.flip && ep.flip[col];
-        }
-        const int64_t wi0 = (n0 + wn * TN * 32) >> 5;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            unsigned mine[TN];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                mine[j] = 0;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int x = (int)acc[i][j][r] - corr;
-                    const bool bit = cok[j] && ((x > thr[j]) != flip[j]);
-                    const unsigned long long mask = __ballot(bit);
-                    const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
-                    if (l32 == r) mine[j] = word;
-                }
+            for (int r = 0; r < SB; ++r) {
+                const int idx = t + 256 * r;
+                *reinterpret_cast<uint4 *>(Bs + (idx / UPR) * LS + (idx % UPR) * 4) = pb[r];
             }
-            const int64_t row = rbase + i * 32 + (l32 >> 2) * 8 + (l32 & 3);
-            if (l32 < 16 && row < M) {
-                uint32_t *dst = ep.packed + row * nw + wi0;
-                if (TN == 2 && (nw & 1) == 0 && wi0 + 1 < nw) {
-                    *reinterpret_cast<uint2 *>(dst) = make_uint2(mine[0], mine[TN - 1]);
-                } else if (TN == 4 && (nw & 3) == 0 && wi0 + 3 < nw) {
-                    *reinterpret_cast<uint4 *>(dst) = make_uint4(mine[0], mine[1 % TN], mine[2 % TN], mine[3 % TN]);
-                } else {
+            __syncthreads();
+            if (kc + 1 < nchunks) prefetch((kc + 1) * KC);
+
+            // a chunk = NG groups of 8 words; lane half h owns words [8g + 4h, 8g + 4h + 4).
+            // Operands of step s+1 are expanded on the VALU while the matrix core runs step s.
+            uint4 wa[NG][TM], wb[NG][TN];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) wa[g][i] = *reinterpret_cast<const uint4 *>(a_rd + i * 32 * LS + g * 8);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) wb[g][j] = *reinterpret_cast<const uint4 *>(b_rd + j * 32 * LS + g * 8);
+            }
+            v8i a[2][TM], b[2][TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[0][i] = expand_fp4(wa[0][i].x, sgn, one);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[0][j] = expand_fp4(wb[0][j].x, sgn, one);
+#pragma unroll
+            for (int st = 0; st < NST; ++st) {
+                const int cur = st & 1, nxt = cur ^ 1;
+                if (st + 1 < NST) {
+                    const int g = (st + 1) >> 2, q = (st + 1) & 3;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) a[nxt][i] = expand_fp4(word_of(wa[g][i], q), sgn, one);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) b[nxt][j] = expand_fp4(word_of(wb[g][j], q), sgn, one);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        if (wi0 + j < nw) dst[j] = mine[j];
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            a[cur][i], b[cur][j], acc[i][j], 4, 4, 0, 0, 0, 0);
+                // interleave: one MFMA, then its share of the next step's VALU work
+#pragma unroll
+                for (int k = 0; k < TM * TN; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
+                }
+            }
+        }
+
+        // ---- epilogue.  Accumulator register r of lane (l32, half) in tile (i, j) is
+        // row 32i + 8(r/4) + 4*half + r%4, column 32j + l32.
+        const int64_t rbase = m0 + wm * TM * 32 + half * 4;
+        const int64_t cbase = n0 + wn * TN * 32 + l32;
+        if (ep.preact) {
+            if (TM * TN >= 16 && m0 + BM <= M && n0 + BN <= N && (int64_t)(BM - 1) * N + BN <= 0x1fffffffLL) {
+                // A whole tile inside C: the stores go through a buffer resource over the tile's
+                // part of C, so that a store is one conversion and one instruction -- the lane's part
+                // of the address is fixed, the row of a register is a scalar offset, the column tile
+                // an immediate.  Streaming stores: C is not read again by this kernel.
+                const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
+                    ep.preact + (m0 * N + n0), 0, (int)(((int64_t)(BM - 1) * N + BN) * 4), 0x00020000);
+                const unsigned row_bytes = (unsigned)N * 4u;
+                const unsigned c_voff = (unsigned)(((wm * TM * 32 + half * 4) * (unsigned)N + wn * TN * 32 + l32) * 4u);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const unsigned soff = (unsigned)(i * 32 + (r >> 2) * 8 + (r & 3)) * row_bytes;
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            __builtin_amdgcn_raw_buffer_store_b32((int)acc[i][j][r] - corr, crs, c_voff + j * 128, soff,
+                                                                  2 /* nontemporal */);
+                    }
+            } else {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int64_t col = cbase + j * 32;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int64_t row = rbase + i * 32 + (r >> 2) * 8 + (r & 3);
+                            if (row < M && col < N) ep.preact[row * N + col] = (int)acc[i][j][r] - corr;
+                        }
+                    }
+            }
+        }
+        if (ep.packed) {
+            // A ballot over the 32 columns of a tile is the packed word of one row (one per lane
+            // half).  Lane r of each half keeps the word of register r, so that a tile's 32 words
+            // leave with one store instruction per row block instead of one per word.
+            const int64_t nw = (N + 31) >> 5;
+            int thr[TN];
+            bool flip[TN], cok[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t col = cbase + j * 32;
+                cok[j] = col < N;
+                thr[j] = cok[j] ? ep.thr[col] : 0;
+                flip[j] = cok[j] && ep.flip && ep.flip[col];
+            }
+            const int64_t wi0 = (n0 + wn * TN * 32) >> 5;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                unsigned mine[TN];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    mine[j] = 0;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int x = (int)acc[i][j][r] - corr;
+                        const bool bit = cok[j] && ((x > thr[j]) != flip[j]);
+                        const unsigned long long mask = __ballot(bit);
+                        const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
+                        if (l32 == r) mine[j] = word;
+                    }
+                }
+                const int64_t row = rbase + i * 32 + (l32 >> 2) * 8 + (l32 & 3);
+                if (l32 < 16 && row < M) {
+                    uint32_t *dst = ep.packed + row * nw + wi0;
+                    if (TN == 2 && (nw & 1) == 0 && wi0 + 1 < nw) {
+                        *reinterpret_cast<uint2 *>(dst) = make_uint2(mine[0], mine[TN - 1]);
+                    } else if (TN == 4 && (nw & 3) == 0 && wi0 + 3 < nw) {
+                        *reinterpret_cast<uint4 *>(dst) = make_uint4(mine[0], mine[1 % TN], mine[2 % TN], mine[3 % TN]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            if (wi0 + j < nw) dst[j] = mine[j];
+                    }
                 }
             }
         }
@@ -351,16 +409,20 @@ template <int TM, int TN>
 bnn_status launch_mfma(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n, int kw,
                        const EpiArgs &ep, hipStream_t s)
 {
-    const int nbn = (int)ceil_div64(n, 64 * TN);
-    const int64_t blocks = nbn * ceil_div64(m, 64 * TM);
+    GemmWalk gw;
+    const int64_t nbm = ceil_div64(m, 64 * TM), nbn = ceil_div64(n, 64 * TN);
+    const int64_t blocks = nbm * nbn;
     if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+    gw.nbm = (int)nbm; gw.nbn = (int)nbn;
+    // two or more rounds of the 256 x 256 tile: the first round starts spread over 10 us
+    gw.stagger_ticks = (TM * TN >= 16 && blocks >= 512) ? gemm_stagger_ticks(1000) : 0;
     dim3 grid((unsigned)blocks);
     if ((kw & 3) == 0)
-        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 4>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 4>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, gw, ep);
     else if ((kw & 1) == 0)
-        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 2>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 2>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, gw, ep);
     else
-        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 1>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+        hipLaunchKernelGGL((bgemm_mfma<TM, TN, 1>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, gw, ep);
     return hip_result(hipGetLastError());
 }
 
