@@ -471,6 +471,242 @@ __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int
     }
 }
 
+// ---- 3x3 kernels, one ring of padding, images of a few KB: whole images in LDS.
+//
+// conv_first_mfma stages, per 256-pixel tile, the tile's input patch byte by byte (every byte has
+// its own bounds test); for the benchmark's first layers that staging, not the arithmetic, is
+// most of the kernel.  Here a block copies whole images (contiguous in memory: 16-byte loads, no
+// index arithmetic) into LDS slots and then takes the 256-pixel tiles of those images one after
+// the other.  Rows above and below an image fall into the slot's pad regions, which are filled
+// with pad_value once per block; the columns left and right of the image are patched into the
+// gathered operand with a per-lane byte mask (a lane's pixel column does not change: a tile
+// spans the whole image width).  Work unit = (image group, run of TPB consecutive tiles); the
+// next unit's images are requested before the current unit is computed and stored to the other
+// LDS buffer afterwards.  MFMA, epilogue and deferred copy-out are those of conv_first_mfma's
+// straight-line variant: K = [kernel row][3 * c_in bytes, padded to 16], two kernel rows per
+// K step (the second step's upper half meets zero weights).
+struct FirstGeomI {
+    int n, h, c_in, c_out, pad_value;
+    int lth, ltw, ni;           // tile = (1 << lth) rows x (1 << ltw = image width) columns x ni images
+    int tiles_y, tpb, cpg;      // tiles per image group, tiles per work unit, work units per image group
+    int n_groups, n_units;
+    int img_bytes;              // h * w * c_in, a multiple of 16
+    int front, slot_bytes;      // pad bytes before an image in its LDS slot (multiple of 16) / slot size
+    int buf_bytes;              // ni * slot_bytes
+    unsigned mg_upi, mg_cpg;    // magic_floor of 16-byte units per image, of cpg
+};
+
+template <int NG, int NU>
+__global__ __launch_bounds__(256, 4) void conv_first_img(const int8_t *__restrict__ in, const int8_t *__restrict__ wt,
+                                                         FirstGeomI g, EpiArgs ep)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int NS = 2, TN = 2, BW = 2 * NG, WS = NS * 32 + 16;
+    unsigned char *Wl = smem;                                                    // [64*NG][WS]
+    uint32_t *Ol = reinterpret_cast<uint32_t *>(smem + 64 * NG * WS);            // [2][256][BW]
+    int *Tl = reinterpret_cast<int *>(smem + 64 * NG * WS + 2 * 256 * BW * 4);   // [64*NG] start values
+    unsigned char *Pl = smem + 64 * NG * WS + 2 * 256 * BW * 4 + 64 * NG * 4;    // [2][ni] image slots
+
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int o_blk = (int)blockIdx.y * 64 * NG;
+    const int w = 1 << g.ltw, th = 1 << g.lth;
+    const int row_bytes = w * g.c_in;
+
+    // ---- work units: unit u = image group u / cpg, tiles [(u % cpg) * tpb, + tpb)
+    auto group_of = [&](int u) { return div_by(u, g.cpg, g.mg_cpg); };
+    // 16-byte units of a group's images: unit -> (image slot, offset); branch-free loads, a unit
+    // beyond the last image of the batch reads the tensor's first bytes (never used: its pixels
+    // are not stored)
+    uint4 vn[NU];
+    auto load_group = [&](int grp) {
+        const int valid = min(g.ni, g.n - grp * g.ni) * g.img_bytes;
+        const int8_t *src = in + (int64_t)grp * g.ni * g.img_bytes;
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int byte = (u * 256 + t) * 16;
+            vn[u] = *reinterpret_cast<const uint4 *>(byte < valid ? src + byte : in);
+        }
+    };
+    auto store_group = [&](int buf) {
+        const int upi = g.img_bytes >> 4;
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int unit = u * 256 + t;
+            const int il = div_by(unit, upi, g.mg_upi);
+            if (il < g.ni)
+                *reinterpret_cast<uint4 *>(Pl + buf * g.buf_bytes + il * g.slot_bytes + g.front + (unit - il * upi) * 16) = vn[u];
+        }
+    };
+    const int first_unit = (int)blockIdx.x;
+    if (first_unit < g.n_units) load_group(group_of(first_unit));
+
+    // ---- pad regions of every slot of both buffers, once per block
+    {
+        const unsigned pv = (unsigned)(uint8_t)(int8_t)g.pad_value * 0x01010101u;
+        const int padw = (g.slot_bytes - g.img_bytes) >> 2, frontw = g.front >> 2;
+        const unsigned mg = magic_floor(padw);
+        for (int idx = t; idx < 2 * g.ni * padw; idx += 256) {
+            const int slot = div_by(idx, padw, mg), j = idx - slot * padw;
+            const int off = j < frontw ? j * 4 : g.img_bytes + j * 4;
+            *reinterpret_cast<unsigned *>(Pl + slot * g.slot_bytes + off) = pv;
+        }
+    }
+
+    // ---- this lane's two pixels (window-major rows of the implicit GEMM): where the 16 operand
+    // bytes of (pixel tile i, K step ks) start inside an image buffer, relative to the unit's
+    // first tile row, and the bytes of the operand that lie left or right of the image
+    int gd[2][NS];
+    unsigned gsh[2][NS], edge[2][3];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int p = wave * 64 + i * 32 + l32;
+        const int wq = p >> 2, sub = p & 3;
+        const int wx = wq & ((w >> 1) - 1);
+        const int wy = (wq >> (g.ltw - 1)) & ((th >> 1) - 1);
+        const int il = wq >> (g.ltw - 1 + g.lth - 1);
+        const int py = 2 * wy + (sub >> 1), px = 2 * wx + (sub & 1);
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks) {
+            const int ti = 2 * ks + half;
+            const int addr = ti < 3 ? il * g.slot_bytes + g.front + (py + ti - 1) * row_bytes + (px - 1) * g.c_in : 0;
+            gd[i][ks] = addr >> 2;
+            gsh[i][ks] = (unsigned)addr & 3u;
+        }
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            unsigned m = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int byte = 4 * q + b;
+                const bool out = (px == 0 && byte < g.c_in) || (px == w - 1 && byte >= 2 * g.c_in && byte < 3 * g.c_in);
+                m |= out ? 0xffu << (8 * b) : 0u;
+            }
+            edge[i][q] = m;
+        }
+    }
+    const unsigned padv4 = (unsigned)(uint8_t)(int8_t)g.pad_value * 0x01010101u;
+    const unsigned char *wlane = Wl + l32 * WS + half * 16;     // this lane's bytes of a weight row tile
+
+    // ---- weights of this block's channels, K-padded: one thread per (channel, kernel row) slot of
+    // 16 bytes (3 * c_in source bytes, contiguous in memory); the K padding behind the third
+    // kernel row is zeroed separately
+    {
+        const int sl = 3 * g.c_in, k_total = 3 * sl;
+        const __amdgpu_buffer_rsrc_t wr =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(wt), 0, g.c_out * k_total, 0x00020000);
+        for (int pair = t; pair < 64 * NG * 3; pair += 256) {
+            const int row = pair / 3, ti = pair - row * 3;
+            const int base = (o_blk + row) * k_total + ti * sl;
+            unsigned v[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) v[q] = __builtin_amdgcn_raw_buffer_load_b8(wr, base + q, 0, 0);
+            unsigned wd[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int nvalid = sl - 4 * k;
+                const unsigned mask = nvalid >= 4 ? 0xffffffffu : (nvalid <= 0 ? 0u : (1u << (8 * nvalid)) - 1u);
+                wd[k] = (v[4 * k] | (v[4 * k + 1] << 8) | (v[4 * k + 2] << 16) | (v[4 * k + 3] << 24)) & mask;
+            }
+            *reinterpret_cast<uint4 *>(Wl + row * WS + ti * 16) = make_uint4(wd[0], wd[1], wd[2], wd[3]);
+        }
+        for (int row = t; row < 64 * NG; row += 256)
+            *reinterpret_cast<uint4 *>(Wl + row * WS + 48) = make_uint4(0u, 0u, 0u, 0u);
+    }
+    StepWords<TN> sw[NG];
+    if (ep.packed) {
+#pragma unroll
+        for (int grp = 0; grp < NG; ++grp) sw[grp] = load_step_words<TN>(ep, o_blk + grp * 64, l32, g.c_out);
+    }
+    stage_bias_i32(ep, o_blk, 64 * NG, g.c_out, 1 << 30, Tl, t);
+    if (first_unit < g.n_units) store_group(0);
+
+    auto tile_pos = [&](int grp, int ty) {
+        TilePos pos;
+        pos.n = g.n; pos.h = g.h; pos.w = w; pos.c_out = g.c_out;
+        pos.lth = g.lth; pos.ltw = g.ltw; pos.img0 = grp * g.ni; pos.y0 = ty * th; pos.x0 = 0;
+        return pos;
+    };
+    TilePos prev = tile_pos(0, 0);
+    const CopyLane copy_lane = make_copy_lane(256, prev, ep.pool, t);
+
+    int it = 0, ui = 0;
+    for (int unit = first_unit; unit < g.n_units; unit += (int)gridDim.x, ++ui) {
+        const int grp = group_of(unit);
+        const int ty0 = (unit - grp * g.cpg) * g.tpb;
+        const int next_unit = unit + (int)gridDim.x;
+        const unsigned *P32 = reinterpret_cast<const unsigned *>(Pl + (ui & 1) * g.buf_bytes);
+        for (int k = 0; k < g.tpb; ++k, ++it) {
+            const int ty = ty0 + k;
+            uint32_t *Oc = Ol + (it & 1) * (256 * BW);
+            __syncthreads();      // the unit's images (first tile) / nothing reads the previous tile's words any more
+            if (k == 0 && next_unit < g.n_units) load_group(group_of(next_unit));
+            if (ep.packed && it > 0)
+                conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), copy_lane, o_blk >> 5, prev, ep);
+            const TilePos pos = tile_pos(grp, ty);
+            prev = pos;
+            const int tile_dw = (ty * th * row_bytes) >> 2;       // a tile's rows are a multiple of four bytes
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                v4i a[NS];
+#pragma unroll
+                for (int ks = 0; ks < NS; ++ks) {
+                    const int d = gd[i][ks] + tile_dw;
+                    const unsigned sh = gsh[i][ks];
+                    const unsigned w0 = P32[d], w1 = P32[d + 1], w2 = P32[d + 2], w3 = P32[d + 3], w4 = P32[d + 4];
+                    const unsigned b0 = __builtin_amdgcn_alignbyte(w1, w0, sh), b1 = __builtin_amdgcn_alignbyte(w2, w1, sh);
+                    const unsigned b2 = __builtin_amdgcn_alignbyte(w3, w2, sh), b3 = __builtin_amdgcn_alignbyte(w4, w3, sh);
+                    a[ks][0] = (int)((b0 & ~edge[i][0]) | (padv4 & edge[i][0]));
+                    a[ks][1] = (int)((b1 & ~edge[i][1]) | (padv4 & edge[i][1]));
+                    a[ks][2] = (int)((b2 & ~edge[i][2]) | (padv4 & edge[i][2]));
+                    a[ks][3] = (int)b3;
+                }
+                const int row0 = wave * 64 + i * 32;
+#pragma unroll
+                for (int cg = 0; cg < NG; ++cg) {
+                    __builtin_amdgcn_s_setprio(1);           // multiplies outrank other waves' epilogues
+                    const int *Tg = Tl + cg * 64;
+                    v16i acc[TN];
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[j] = load_bias16<v16i>(Tg + j * 32, half);
+#pragma unroll
+                    for (int ks = 0; ks < NS; ++ks)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const v4i b = *reinterpret_cast<const v4i *>(wlane + (cg * TN + j) * 32 * WS + ks * 32);
+                            acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a[ks], acc[j], 0, 0, 0);   // rows = channels
+                        }
+                    __builtin_amdgcn_s_setprio(0);
+                    const int ch0 = o_blk + cg * 64;
+                    if (ep.preact) {
+                        auto getx = [&](int, int j, int r) {
+                            return acc[j][r] - Tg[j * 32 + (r >> 2) * 8 + half * 4 + (r & 3)];
+                        };
+                        conv_tile_store_preact<1, TN>(getx, row0, ch0, l32, half, pos, ep.preact);
+                    }
+                    if (ep.packed) {
+                        StepWords<TN> cursw = sw[0];
+#pragma unroll
+                        for (int q = 1; q < NG; ++q)
+                            if (cg == q) cursw = sw[q];
+                        auto gets = [&](int, int j, int r) { return acc[j][r]; };
+                        conv_tile_step_to_lds<1, TN>(gets, row0, cg * TN, BW, l32, half, cursw, ep.pool,
+                                                     ep.pool_first != 0, Oc);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);      // one group's registers at a time
+                }
+            }
+        }
+        // the other buffer was last read one unit ago, and every wave has passed a barrier since
+        if (next_unit < g.n_units) store_group((ui + 1) & 1);
+    }
+    if (ep.packed && it > 0) {
+        __syncthreads();
+        conv_tile_copy_out<BW>(Ol + ((it - 1) & 1) * (256 * BW), copy_lane, o_blk >> 5, prev, ep);
+    }
+}
+
 // 1x1, pad 0, c_in % 16 == 0: int8 GEMM  X[m][o] = sum_c A[m][c] * W[o][c];  m = pixel index.
 // Block = 2 x 2 waves, one 32 x 32 tile each; operands are 16-byte global loads.
 __global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ A, const int8_t *__restrict__ Wt,
@@ -558,6 +794,61 @@ bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, 
     return hip_result(hipGetLastError());
 }
 
+// Whole-image kernel: 3x3, one ring of padding, at most four input channels, image width a power
+// of two that a 256-pixel tile spans, image groups of at most 16 KB.  BNN_ERR_UNSUPPORTED otherwise.
+template <int NG>
+bnn_status launch_first_img(const int8_t *in, const int8_t *wt, int n, int h, int w, int c_in, int c_out,
+                            int pad_value, const EpiArgs &ep, hipStream_t s)
+{
+    // a 256-pixel tile spans the whole image width (a power of two, 2 .. 128); it takes 256 / w rows
+    // of one image, or whole images when they have fewer than 256 pixels (height a power of two then)
+    auto log2_exact = [](int v) { int l = 0; while ((1 << l) < v) ++l; return (1 << l) == v ? l : -1; };
+    const int ltw = log2_exact(w);
+    if (ltw < 1 || ltw > 7) return BNN_ERR_UNSUPPORTED;
+    int lth = 8 - ltw, ni = 1;
+    if (h < (1 << lth)) {
+        lth = log2_exact(h);
+        if (lth < 1) return BNN_ERR_UNSUPPORTED;
+        ni = 256 >> (ltw + lth);
+    } else if (h % (1 << lth) != 0) {
+        return BNN_ERR_UNSUPPORTED;
+    }
+    const int th = 1 << lth;
+    FirstGeomI g;
+    g.n = n; g.h = h; g.c_in = c_in; g.c_out = c_out; g.pad_value = pad_value;
+    g.lth = lth; g.ltw = ltw; g.ni = ni;
+    g.img_bytes = h * w * c_in;
+    if ((g.img_bytes & 15) != 0 || (int64_t)g.ni * g.img_bytes > 16384) return BNN_ERR_UNSUPPORTED;
+    const int row_bytes = w * c_in;
+    g.front = (row_bytes + c_in + 15) & ~15;
+    g.slot_bytes = (g.front + g.img_bytes + row_bytes + c_in + 32 + 15) & ~15;   // gathers read 20 bytes past a row's start
+    g.buf_bytes = g.ni * g.slot_bytes;
+    g.tiles_y = ni == 1 ? h / th : 1;
+    g.n_groups = (n + g.ni - 1) / g.ni;
+    const int n_co_tiles = (c_out + 64 * NG - 1) / (64 * NG);
+    // tiles per work unit: as many as still leave four blocks for every compute unit
+    g.tpb = 1;
+    for (int d = g.tiles_y; d >= 1; --d)
+        if (g.tiles_y % d == 0 && (int64_t)g.n_groups * (g.tiles_y / d) * n_co_tiles >= 1024) { g.tpb = d; break; }
+    g.cpg = g.tiles_y / g.tpb;
+    const int64_t units = (int64_t)g.n_groups * g.cpg;
+    if (units > 0x3fffffffLL || n_co_tiles > 65535) return BNN_ERR_UNSUPPORTED;
+    g.n_units = (int)units;
+    g.mg_upi = magic_floor(g.img_bytes >> 4);
+    g.mg_cpg = magic_floor(g.cpg);
+    const size_t smem = (size_t)64 * NG * 80 + 2 * 256 * 2 * NG * 4 + 64 * NG * 4 + (size_t)2 * g.buf_bytes;
+    if (smem > 40 * 1024) return BNN_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)(units < 1024 ? units : 1024), (unsigned)n_co_tiles);
+    const int group_bytes = g.ni * g.img_bytes;
+    if (group_bytes <= 4096)
+        hipLaunchKernelGGL((conv_first_img<NG, 1>), grid, dim3(256), smem, s, in, wt, g, ep);
+    else if (group_bytes <= 8192)
+        hipLaunchKernelGGL((conv_first_img<NG, 2>), grid, dim3(256), smem, s, in, wt, g, ep);
+    else
+        hipLaunchKernelGGL((conv_first_img<NG, 4>), grid, dim3(256), smem, s, in, wt, g, ep);
+    return hip_result(hipGetLastError());
+}
+
 }  // namespace
 
 bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_in, const int8_t *wt,
@@ -575,6 +866,15 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
             hipLaunchKernelGGL(fc_first_mfma, dim3((unsigned)blocks), dim3(256), 0, s, in, wt, M, c_out, c_in, ep);
             return hip_result(hipGetLastError());
         }
+    }
+    // 3x3 over small images: whole images in LDS
+    if (kh == 3 && kw == 3 && pad == 1 && c_in <= 4 && (int64_t)n * h * w * c_in < 0x7fffffff00LL) {
+        const TileShape ts = make_tile_shape(ho_, wo_, 256);
+        const int64_t ptiles = (int64_t)ts.tiles_x * ts.tiles_y * ((n + ts.ni - 1) / ts.ni);
+        const bool two_groups = c_out > 64 && ptiles * ((c_out + 127) / 128) >= 256;
+        const bnn_status st = two_groups ? launch_first_img<2>(in, wt, n, h, w, c_in, c_out, pad_value, ep, s)
+                                         : launch_first_img<1>(in, wt, n, h, w, c_in, c_out, pad_value, ep, s);
+        if (st != BNN_ERR_UNSUPPORTED) return st;
     }
     // small kernels: patch + weights in LDS, matrix cores
     {

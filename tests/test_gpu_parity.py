@@ -216,7 +216,15 @@ FIRST_SHAPES = [(2, 28, 28, 1, 64, 3, 3, 1, -1, 2), (2, 32, 32, 3, 128, 3, 3, 1,
                 (1, 300, 4, 1, 8, 3, 3, 200, -1, 2), (1, 6, 6, 2, 16, 3, 3, 130, 3, 1),
                 # 1x1 layer with exactly one 16-byte slice per row (K = 16), last row included
                 (3, 1, 1, 16, 40, 1, 1, 0, -1, 1), (70, 1, 1, 16, 64, 1, 1, 0, -1, 1),
-                (5, 1, 1, 48, 33, 1, 1, 0, -1, 1)]
+                (5, 1, 1, 48, 33, 1, 1, 0, -1, 1),
+                # 3x3 over small power-of-two-wide images (whole images in LDS): one and two channel
+                # groups per block, several images per tile with a ragged last group, several tiles and
+                # several work units per block, image groups of 4 / 8 / 16 KB, every pad value
+                (5, 32, 32, 3, 128, 3, 3, 1, -1, 1), (70, 32, 32, 3, 128, 3, 3, 1, 7, 2),
+                (9, 16, 16, 4, 64, 3, 3, 1, 0, 2), (33, 8, 8, 1, 40, 3, 3, 1, -1, 1),
+                (3, 64, 32, 3, 96, 3, 3, 1, 3, 1), (2, 128, 128, 1, 32, 3, 3, 1, -1, 2),
+                (300, 4, 4, 2, 16, 3, 3, 1, -1, 2), (1100, 32, 32, 3, 128, 3, 3, 1, -1, 1),
+                (1300, 16, 16, 3, 64, 3, 3, 1, -128, 2)]
 
 
 @pytest.mark.parametrize("n,h,w,ci,co,kh,kw,pad,padv,pool", FIRST_SHAPES)
