@@ -67,11 +67,13 @@ def time_steps(fn, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps, (t1 - t0) * 1e3 / steps
 
 
+MAX_LAUNCHES = None      # --max-launches: cap for counter-collection runs, where every dispatch is serialised
+
+
 def iters_for(us_estimate):
     """>= 1000 launches for sub-100 us work, fewer for long kernels (about 0.1 - 0.3 s per shape)."""
-    if us_estimate < 100:
-        return 1000
-    return int(max(20, min(1000, 200e3 / us_estimate)))
+    n = 1000 if us_estimate < 100 else int(max(20, min(1000, 200e3 / us_estimate)))
+    return min(n, MAX_LAUNCHES) if MAX_LAUNCHES else n
 
 
 def latency_stats(fn, n, torch):
@@ -127,7 +129,8 @@ def section_gemv(P, W, torch):
     b = torch.randint(-2**31, 2**31 - 1, (n, k // 32), dtype=torch.int32, device="cuda", generator=g)
     c = torch.empty((m, n), dtype=torch.int32, device="cuda")
     fn = lambda: P.bnn_fc_binary(a, m, k, b, n, c_out=c)
-    ev, _ = time_steps(fn, 1000, 10, torch)
+    warm_n = iters_for(10)
+    ev, _ = time_steps(fn, warm_n, 10, torch)
     alg_bytes = (m + n) * k / 8 + 4 * m * n
     flush = torch.empty(512 * 1024 * 1024 // 4, dtype=torch.int32, device="cuda")
     cold = []
@@ -145,7 +148,7 @@ def section_gemv(P, W, torch):
     cold_us = cold[len(cold) // 2]
     del flush
     out = {"m": m, "n": n, "k": k, "algorithmic_bytes": int(alg_bytes),
-           "warm": {"us": round(ev * 1e3, 2), "launches": 1000, "GBs": round(alg_bytes / (ev * 1e-3) / 1e9, 1),
+           "warm": {"us": round(ev * 1e3, 2), "launches": warm_n, "GBs": round(alg_bytes / (ev * 1e-3) / 1e9, 1),
                     "frac_hbm_peak": round(alg_bytes / (ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                     "note": "back to back, B resident in L2 / memory-side cache"},
            "cold": {"us": round(cold_us, 2), "launches": len(cold), "GBs": round(alg_bytes / (cold_us * 1e-6) / 1e9, 1),
@@ -301,10 +304,14 @@ def main():
     ap.add_argument("--only", choices=SECTIONS, help="run one extra section alone (for profiling) and print it")
     ap.add_argument("--cpu-images", type=int, default=640,
                     help="images in the CPU-oracle sample (640 images of the default workload are about 12 s of host work)")
+    ap.add_argument("--max-launches", type=int, default=None,
+                    help="cap on launches per shape in the extra sections (for rocprofv3 --pmc runs)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
 
+    global MAX_LAUNCHES
+    MAX_LAUNCHES = args.max_launches
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (batch sharding needs no collective and is "
               "not part of it); run with --gpus 1", file=sys.stderr)

@@ -519,28 +519,61 @@ __global__ __launch_bounds__(256, 4) void conv_first_img(const int8_t *__restric
     // 16-byte units of a group's images: unit -> (image slot, offset); branch-free loads, a unit
     // beyond the last image of the batch reads the tensor's first bytes (never used: its pixels
     // are not stored)
-    uint4 vn[NU];
+    // (named registers, not an array: the loads sit inside a conditional and an array would be
+    // kept in scratch memory)
+    uint4 vn0, vn1;
+    vn0 = vn1 = make_uint4(0u, 0u, 0u, 0u);
+    auto load_unit = [&](int u, int64_t src, int valid) {
+        const int byte = (u * 256 + t) * 16;
+        return *reinterpret_cast<const uint4 *>(in + (byte < valid ? src + byte : (int64_t)0));
+    };
     auto load_group = [&](int grp) {
         const int valid = min(g.ni, g.n - grp * g.ni) * g.img_bytes;
-        const int8_t *src = in + (int64_t)grp * g.ni * g.img_bytes;
-#pragma unroll
-        for (int u = 0; u < NU; ++u) {
-            const int byte = (u * 256 + t) * 16;
-            vn[u] = *reinterpret_cast<const uint4 *>(byte < valid ? src + byte : in);
-        }
+        const int64_t src = (int64_t)grp * g.ni * g.img_bytes;
+        vn0 = load_unit(0, src, valid);
+        if constexpr (NU > 1) vn1 = load_unit(1, src, valid);
+    };
+    auto store_unit = [&](int u, int buf, const uint4 &v) {
+        const int upi = g.img_bytes >> 4;
+        const int unit = u * 256 + t;
+        const int il = div_by(unit, upi, g.mg_upi);
+        if (il < g.ni)
+            *reinterpret_cast<uint4 *>(Pl + buf * g.buf_bytes + il * g.slot_bytes + g.front + (unit - il * upi) * 16) = v;
     };
     auto store_group = [&](int buf) {
-        const int upi = g.img_bytes >> 4;
-#pragma unroll
-        for (int u = 0; u < NU; ++u) {
-            const int unit = u * 256 + t;
-            const int il = div_by(unit, upi, g.mg_upi);
-            if (il < g.ni)
-                *reinterpret_cast<uint4 *>(Pl + buf * g.buf_bytes + il * g.slot_bytes + g.front + (unit - il * upi) * 16) = vn[u];
-        }
+        store_unit(0, buf, vn0);
+        if constexpr (NU > 1) store_unit(1, buf, vn1);
     };
+    // ---- prologue.  Every global load of the prologue (first images, weights, thresholds, flips)
+    // is issued before the first of them is waited for: one memory latency instead of four.
     const int first_unit = (int)blockIdx.x;
     if (first_unit < g.n_units) load_group(group_of(first_unit));
+
+    // weights of this block's channels, K-padded: one thread per (channel, kernel row) slot of 16
+    // bytes (3 * c_in source bytes, contiguous in memory) through a buffer resource over the weight
+    // tensor: slots of channels past c_out, and of the rounds' unused threads, address past its end
+    // and read zeros
+    constexpr int NPAIR = 64 * NG * 3, NR = (NPAIR + 255) / 256;
+    const int sl = 3 * g.c_in, k_total = 3 * sl;
+    const __amdgpu_buffer_rsrc_t wr =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(wt), 0, g.c_out * k_total, 0x00020000);
+    unsigned wv[NR][16];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const int pair = t + 256 * r;
+        const int row = pair / 3, ti = pair - row * 3;
+        const int base = pair < NPAIR ? (o_blk + row) * k_total + ti * sl : 0x7ffffff0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) wv[r][q] = __builtin_amdgcn_raw_buffer_load_b8(wr, base + q, 0, 0);
+    }
+    // threshold of channel t of the block (start value of its accumulators), flips
+    int thr_t = 0;
+    if (ep.packed && t < 64 * NG && o_blk + t < g.c_out) thr_t = ep.thr[o_blk + t];
+    StepWords<TN> sw[NG];
+    if (ep.packed) {
+#pragma unroll
+        for (int grp = 0; grp < NG; ++grp) sw[grp] = load_step_words<TN>(ep, o_blk + grp * 64, l32, g.c_out);
+    }
 
     // ---- pad regions of every slot of both buffers, once per block
     {
@@ -589,37 +622,32 @@ __global__ __launch_bounds__(256, 4) void conv_first_img(const int8_t *__restric
     const unsigned padv4 = (unsigned)(uint8_t)(int8_t)g.pad_value * 0x01010101u;
     const unsigned char *wlane = Wl + l32 * WS + half * 16;     // this lane's bytes of a weight row tile
 
-    // ---- weights of this block's channels, K-padded: one thread per (channel, kernel row) slot of
-    // 16 bytes (3 * c_in source bytes, contiguous in memory); the K padding behind the third
-    // kernel row is zeroed separately
-    {
-        const int sl = 3 * g.c_in, k_total = 3 * sl;
-        const __amdgpu_buffer_rsrc_t wr =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(wt), 0, g.c_out * k_total, 0x00020000);
-        for (int pair = t; pair < 64 * NG * 3; pair += 256) {
-            const int row = pair / 3, ti = pair - row * 3;
-            const int base = (o_blk + row) * k_total + ti * sl;
-            unsigned v[16];
+    // ---- what was loaded goes to LDS: weight slots (the bytes behind a kernel row's 3 * c_in
+    // belong to the next row and are masked off; the K padding behind the third row is zero),
+    // accumulator start values -(threshold) - 1 (see stage_bias_i32), the first images
 #pragma unroll
-            for (int q = 0; q < 16; ++q) v[q] = __builtin_amdgcn_raw_buffer_load_b8(wr, base + q, 0, 0);
-            unsigned wd[4];
+    for (int r = 0; r < NR; ++r) {
+        const int pair = t + 256 * r;
+        const int row = pair / 3, ti = pair - row * 3;
+        unsigned wd[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int nvalid = sl - 4 * k;
-                const unsigned mask = nvalid >= 4 ? 0xffffffffu : (nvalid <= 0 ? 0u : (1u << (8 * nvalid)) - 1u);
-                wd[k] = (v[4 * k] | (v[4 * k + 1] << 8) | (v[4 * k + 2] << 16) | (v[4 * k + 3] << 24)) & mask;
-            }
-            *reinterpret_cast<uint4 *>(Wl + row * WS + ti * 16) = make_uint4(wd[0], wd[1], wd[2], wd[3]);
+        for (int k = 0; k < 4; ++k) {
+            const int nvalid = sl - 4 * k;
+            const unsigned mask = nvalid >= 4 ? 0xffffffffu : (nvalid <= 0 ? 0u : (1u << (8 * nvalid)) - 1u);
+            wd[k] = (wv[r][4 * k] | (wv[r][4 * k + 1] << 8) | (wv[r][4 * k + 2] << 16) | (wv[r][4 * k + 3] << 24)) & mask;
         }
-        for (int row = t; row < 64 * NG; row += 256)
-            *reinterpret_cast<uint4 *>(Wl + row * WS + 48) = make_uint4(0u, 0u, 0u, 0u);
+        if (pair < NPAIR) *reinterpret_cast<uint4 *>(Wl + row * WS + ti * 16) = make_uint4(wd[0], wd[1], wd[2], wd[3]);
     }
-    StepWords<TN> sw[NG];
-    if (ep.packed) {
-#pragma unroll
-        for (int grp = 0; grp < NG; ++grp) sw[grp] = load_step_words<TN>(ep, o_blk + grp * 64, l32, g.c_out);
+    if (t < 64 * NG) {
+        *reinterpret_cast<uint4 *>(Wl + t * WS + 48) = make_uint4(0u, 0u, 0u, 0u);
+        int v = 0;
+        if (ep.packed && o_blk + t < g.c_out) {
+            const int bound = 1 << 30;
+            v = thr_t > bound ? bound : (thr_t < -bound ? -bound : thr_t);
+            v = -v - 1;
+        }
+        Tl[t] = v;
     }
-    stage_bias_i32(ep, o_blk, 64 * NG, g.c_out, 1 << 30, Tl, t);
     if (first_unit < g.n_units) store_group(0);
 
     auto tile_pos = [&](int grp, int ty) {
@@ -795,7 +823,7 @@ bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, 
 }
 
 // Whole-image kernel: 3x3, one ring of padding, at most four input channels, image width a power
-// of two that a 256-pixel tile spans, image groups of at most 16 KB.  BNN_ERR_UNSUPPORTED otherwise.
+// of two that a 256-pixel tile spans, image groups of at most 8 KB.  BNN_ERR_UNSUPPORTED otherwise.
 template <int NG>
 bnn_status launch_first_img(const int8_t *in, const int8_t *wt, int n, int h, int w, int c_in, int c_out,
                             int pad_value, const EpiArgs &ep, hipStream_t s)
@@ -818,7 +846,7 @@ bnn_status launch_first_img(const int8_t *in, const int8_t *wt, int n, int h, in
     g.n = n; g.h = h; g.c_in = c_in; g.c_out = c_out; g.pad_value = pad_value;
     g.lth = lth; g.ltw = ltw; g.ni = ni;
     g.img_bytes = h * w * c_in;
-    if ((g.img_bytes & 15) != 0 || (int64_t)g.ni * g.img_bytes > 16384) return BNN_ERR_UNSUPPORTED;
+    if ((g.img_bytes & 15) != 0 || (int64_t)g.ni * g.img_bytes > 8192) return BNN_ERR_UNSUPPORTED;
     const int row_bytes = w * c_in;
     g.front = (row_bytes + c_in + 15) & ~15;
     g.slot_bytes = (g.front + g.img_bytes + row_bytes + c_in + 32 + 15) & ~15;   // gathers read 20 bytes past a row's start
@@ -842,10 +870,8 @@ bnn_status launch_first_img(const int8_t *in, const int8_t *wt, int n, int h, in
     const int group_bytes = g.ni * g.img_bytes;
     if (group_bytes <= 4096)
         hipLaunchKernelGGL((conv_first_img<NG, 1>), grid, dim3(256), smem, s, in, wt, g, ep);
-    else if (group_bytes <= 8192)
-        hipLaunchKernelGGL((conv_first_img<NG, 2>), grid, dim3(256), smem, s, in, wt, g, ep);
     else
-        hipLaunchKernelGGL((conv_first_img<NG, 4>), grid, dim3(256), smem, s, in, wt, g, ep);
+        hipLaunchKernelGGL((conv_first_img<NG, 2>), grid, dim3(256), smem, s, in, wt, g, ep);
     return hip_result(hipGetLastError());
 }
 

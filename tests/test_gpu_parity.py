@@ -219,7 +219,7 @@ FIRST_SHAPES = [(2, 28, 28, 1, 64, 3, 3, 1, -1, 2), (2, 32, 32, 3, 128, 3, 3, 1,
                 (5, 1, 1, 48, 33, 1, 1, 0, -1, 1),
                 # 3x3 over small power-of-two-wide images (whole images in LDS): one and two channel
                 # groups per block, several images per tile with a ragged last group, several tiles and
-                # several work units per block, image groups of 4 / 8 / 16 KB, every pad value
+                # several work units per block, image groups of 4 / 8 KB (16 KB: the general kernel), every pad value
                 (5, 32, 32, 3, 128, 3, 3, 1, -1, 1), (70, 32, 32, 3, 128, 3, 3, 1, 7, 2),
                 (9, 16, 16, 4, 64, 3, 3, 1, 0, 2), (33, 8, 8, 1, 40, 3, 3, 1, -1, 1),
                 (3, 64, 32, 3, 96, 3, 3, 1, 3, 1), (2, 128, 128, 1, 32, 3, 3, 1, -1, 2),
