@@ -169,7 +169,7 @@ def section_conv_sweep(P, W, torch, oracle, host_images=16):
 
     n = 1024
     rows = []
-    threads = oracle.max_threads()
+    threads = oracle.max_threads() if oracle is not None else 0
     for hw, c in W.CONV_SWEEP_SHAPES:
         cw = c // 32
         rng = W.rng_for(4, hw, c % 1000)
