@@ -555,16 +555,19 @@ __global__ __launch_bounds__(256, 4) void conv_first_img(const int8_t *__restric
     // and read zeros
     constexpr int NPAIR = 64 * NG * 3, NR = (NPAIR + 255) / 256;
     const int sl = 3 * g.c_in, k_total = 3 * sl;
+    // (the range is rounded up to whole dwords: the last valid byte's dword must not be refused; the
+    // at most three bytes behind the tensor share an aligned dword with it and are masked off)
     const __amdgpu_buffer_rsrc_t wr =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(wt), 0, g.c_out * k_total, 0x00020000);
-    unsigned wv[NR][16];
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(wt), 0, (g.c_out * k_total + 3) & ~3, 0x00020000);
+    unsigned wv[NR][4];
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
         const int pair = t + 256 * r;
         const int row = pair / 3, ti = pair - row * 3;
-        const int base = pair < NPAIR ? (o_blk + row) * k_total + ti * sl : 0x7ffffff0;
+        // the slot's 3 * c_in <= 12 source bytes lie in the four dwords from its start rounded down
+        const int base = pair < NPAIR ? ((o_blk + row) * k_total + ti * sl) & ~3 : 0x7ffffff0;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) wv[r][q] = __builtin_amdgcn_raw_buffer_load_b8(wr, base + q, 0, 0);
+        for (int q = 0; q < 4; ++q) wv[r][q] = __builtin_amdgcn_raw_buffer_load_b32(wr, base + 4 * q, 0, 0);
     }
     // threshold of channel t of the block (start value of its accumulators), flips
     int thr_t = 0;
@@ -607,17 +610,11 @@ __global__ __launch_bounds__(256, 4) void conv_first_img(const int8_t *__restric
             gd[i][ks] = addr >> 2;
             gsh[i][ks] = (unsigned)addr & 3u;
         }
-#pragma unroll
-        for (int q = 0; q < 3; ++q) {
-            unsigned m = 0;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int byte = 4 * q + b;
-                const bool out = (px == 0 && byte < g.c_in) || (px == w - 1 && byte >= 2 * g.c_in && byte < 3 * g.c_in);
-                m |= out ? 0xffu << (8 * b) : 0u;
-            }
-            edge[i][q] = m;
-        }
+        // operand bytes [0, c_in) lie left of the image for px == 0, bytes [2 c_in, 3 c_in) right of it
+        // for px == w - 1 (c_in <= 4: twelve operand bytes, three dwords)
+        const unsigned __int128 field = ((unsigned __int128)1 << (8 * g.c_in)) - 1;
+        const unsigned __int128 m = (px == 0 ? field : 0) | (px == w - 1 ? field << (16 * g.c_in) : 0);
+        edge[i][0] = (unsigned)m; edge[i][1] = (unsigned)(m >> 32); edge[i][2] = (unsigned)(m >> 64);
     }
     const unsigned padv4 = (unsigned)(uint8_t)(int8_t)g.pad_value * 0x01010101u;
     const unsigned char *wlane = Wl + l32 * WS + half * 16;     // this lane's bytes of a weight row tile
@@ -629,12 +626,13 @@ __global__ __launch_bounds__(256, 4) void conv_first_img(const int8_t *__restric
     for (int r = 0; r < NR; ++r) {
         const int pair = t + 256 * r;
         const int row = pair / 3, ti = pair - row * 3;
+        const unsigned sh = (unsigned)((o_blk + row) * k_total + ti * sl) & 3u;
         unsigned wd[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int nvalid = sl - 4 * k;
             const unsigned mask = nvalid >= 4 ? 0xffffffffu : (nvalid <= 0 ? 0u : (1u << (8 * nvalid)) - 1u);
-            wd[k] = (wv[r][4 * k] | (wv[r][4 * k + 1] << 8) | (wv[r][4 * k + 2] << 16) | (wv[r][4 * k + 3] << 24)) & mask;
+            wd[k] = (k < 3 ? __builtin_amdgcn_alignbyte(wv[r][k + 1], wv[r][k], sh) : 0u) & mask;
         }
         if (pair < NPAIR) *reinterpret_cast<uint4 *>(Wl + row * WS + ti * 16) = make_uint4(wd[0], wd[1], wd[2], wd[3]);
     }

@@ -224,7 +224,9 @@ FIRST_SHAPES = [(2, 28, 28, 1, 64, 3, 3, 1, -1, 2), (2, 32, 32, 3, 128, 3, 3, 1,
                 (9, 16, 16, 4, 64, 3, 3, 1, 0, 2), (33, 8, 8, 1, 40, 3, 3, 1, -1, 1),
                 (3, 64, 32, 3, 96, 3, 3, 1, 3, 1), (2, 128, 128, 1, 32, 3, 3, 1, -1, 2),
                 (300, 4, 4, 2, 16, 3, 3, 1, -1, 2), (1100, 32, 32, 3, 128, 3, 3, 1, -1, 1),
-                (1300, 16, 16, 3, 64, 3, 3, 1, -128, 2)]
+                (1300, 16, 16, 3, 64, 3, 3, 1, -128, 2),
+                # weight tensor of 33 * 27 = 891 bytes (not a whole number of dwords), ragged channel tile
+                (6, 8, 8, 3, 33, 3, 3, 1, 5, 1)]
 
 
 @pytest.mark.parametrize("n,h,w,ci,co,kh,kw,pad,padv,pool", FIRST_SHAPES)
