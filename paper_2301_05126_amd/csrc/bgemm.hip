@@ -13,6 +13,8 @@
 //
 //   bgemm_mfma<TM,TN>  block = 2x2 waves, wave tile (32*TM) x (32*TN), K streamed through
 //                      LDS as packed words in chunks of 16 .. 64 words.
+//   bgemm_small        few 64 x 64 tiles: 32 x 32 outputs per block, K split over its four waves,
+//                      operands straight from global memory.
 //   bgemv_rows         m <= 8: bandwidth-bound, xor + popcount on the VALU, four output rows of
 //                      B per wave, halving-butterfly reduction over the 64 lanes.
 // Both end in the same epilogue: optional int32 store, optional threshold/flip/bit-pack.
@@ -54,6 +56,37 @@ __device__ __forceinline__ uint4 load_row_words(const uint32_t *__restrict__ bas
             if (kpos + 2 < kw_total) v.z = p[2];
             if (kpos + 3 < kw_total) v.w = p[3];
         }
+    }
+    return v;
+}
+
+// The same four words without branches, so that many such loads can be in flight together: a
+// word that does not exist reads the tensor's first word and is zeroed afterwards.
+template <int VEC>
+__device__ __forceinline__ uint4 load_row_words_nb(const uint32_t *__restrict__ base, int64_t row,
+                                                   int64_t rows, int kw_total, int kpos)
+{
+    const bool row_ok = row < rows;
+    const int64_t at = row * (int64_t)kw_total + kpos;
+    uint4 v;
+    if (VEC == 4) {
+        const bool ok = row_ok && kpos < kw_total;
+        v = *reinterpret_cast<const uint4 *>(base + (ok ? at : 0));
+        v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
+    } else if (VEC == 2) {
+        const bool ok0 = row_ok && kpos < kw_total, ok1 = row_ok && kpos + 2 < kw_total;
+        const uint2 lo = *reinterpret_cast<const uint2 *>(base + (ok0 ? at : 0));
+        const uint2 hi = *reinterpret_cast<const uint2 *>(base + (ok1 ? at + 2 : 0));
+        v = make_uint4(ok0 ? lo.x : 0u, ok0 ? lo.y : 0u, ok1 ? hi.x : 0u, ok1 ? hi.y : 0u);
+    } else {
+        uint32_t w[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool ok = row_ok && kpos + q < kw_total;
+            const uint32_t x = base[ok ? at + q : 0];
+            w[q] = ok ? x : 0u;
+        }
+        v = make_uint4(w[0], w[1], w[2], w[3]);
     }
     return v;
 }
@@ -306,6 +339,93 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
     }
 }
 
+// Small dense problems (the 64 x 64 tiling would leave most compute units idle): a block owns
+// 32 x 32 outputs and its four waves split K in units of four MFMA steps (eight packed words per
+// row; lane half h owns words [8u + 4h, 8u + 4h + 4) of unit u, one 16-byte load per operand, lane
+// and unit).  Wave v takes the units v, v + 4, ... in rounds of up to eight units with all loads
+// of a round in flight together, straight from global memory (no staging, no barrier before the
+// MFMAs); the partial sums meet in LDS and wave 0 runs the epilogue.  Latency, not throughput:
+// with a quarter of K per wave and four times the blocks, a batch-256 FC layer of K = 8192 takes
+// half the time of the 64 x 64 tile.
+template <int VEC>
+__global__ __launch_bounds__(256) void bgemm_small(const uint32_t *__restrict__ A, const uint32_t *__restrict__ B,
+                                                   int64_t M, int64_t N, int Kw, int K, int nbn, EpiArgs ep)
+{
+    constexpr int UR = 8;                   // units per wave and round
+    __shared__ float red[3][16][64];        // partial sums of waves 1..3
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int64_t m0 = (int64_t)(blockIdx.x / nbn) * 32;
+    const int64_t n0 = (int64_t)(blockIdx.x % nbn) * 32;
+    const int units = (Kw + 7) >> 3;
+
+    uint32_t sgn = 0x88888888u, one = 0x22222222u;
+    asm volatile("" : "+s"(sgn));
+    asm volatile("" : "+v"(one));
+    v16f acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+
+    for (int u0 = wave; u0 < units; u0 += 4 * UR) {
+        uint4 wa[UR], wb[UR];
+#pragma unroll
+        for (int k = 0; k < UR; ++k) {
+            const int u = u0 + 4 * k;
+            // (a unit or a row past the end gives zeros)
+            wa[k] = load_row_words_nb<VEC>(A, m0 + l32, M, Kw, u * 8 + half * 4);
+            wb[k] = load_row_words_nb<VEC>(B, n0 + l32, N, Kw, u * 8 + half * 4);
+        }
+#pragma unroll
+        for (int k = 0; k < UR; ++k) {
+            if (u0 + 4 * k < units) {       // uniform per wave
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        expand_fp4(word_of(wa[k], q), sgn, one), expand_fp4(word_of(wb[k], q), sgn, one), acc, 4, 4,
+                        0, 0, 0, 0);
+            }
+        }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[wave - 1][r][lane] = acc[r];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+#pragma unroll
+        for (int v = 0; v < 3; ++v) acc[r] += red[v][r][lane];      // small integers: exact in any order
+
+    // ---- epilogue of one 32 x 32 tile: register r of lane (l32, half) is row 8(r/4) + 4*half + r%4, column l32
+    const int corr = units * 8 * 32 - K;        // zero words and tail bits all counted as +1
+    const int64_t rbase = m0 + half * 4, col = n0 + l32;
+    const bool cok = col < N;
+    if (ep.preact) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = rbase + (r >> 2) * 8 + (r & 3);
+            if (row < M && cok) ep.preact[row * N + col] = (int)acc[r] - corr;
+        }
+    }
+    if (ep.packed) {
+        const int64_t nw = (N + 31) >> 5;
+        const int thr = cok ? ep.thr[col] : 0;
+        const bool flip = cok && ep.flip && ep.flip[col];
+        unsigned mine = 0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int x = (int)acc[r] - corr;
+            const unsigned long long mask = __ballot(cok && ((x > thr) != flip));
+            const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
+            if (l32 == r) mine = word;          // lane r of each half keeps the word of register r
+        }
+        const int64_t row = rbase + (l32 >> 2) * 8 + (l32 & 3);
+        if (l32 < 16 && row < M) ep.packed[row * nw + (n0 >> 5)] = mine;
+    }
+}
+
 // m <= MT rows of A (batch 1 .. 8): bandwidth / latency bound, on the VALU.
 // Block = 8 waves = 32 consecutive outputs (one packed word); wave w owns outputs 4w..4w+3
 // and streams their B rows with all loads of a K slice in flight at once.  Lanes stride K
@@ -445,6 +565,18 @@ bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint3
     const int64_t want = 192;
     if (ceil_div64(m, 256) * ceil_div64(n, 256) >= want) return launch_mfma<4, 4>(a, m, k, b, n, kw, ep, s);
     if (ceil_div64(m, 128) * ceil_div64(n, 128) >= want) return launch_mfma<2, 2>(a, m, k, b, n, kw, ep, s);
+    // fewer than that many 64 x 64 tiles: 32 x 32 tiles with K split over the block's waves
+    if (ceil_div64(m, 64) * ceil_div64(n, 64) < want) {
+        const int nbn = (int)ceil_div64(n, 32);
+        const dim3 grid((unsigned)(nbn * ceil_div64(m, 32)));
+        if ((kw & 3) == 0)
+            hipLaunchKernelGGL((bgemm_small<4>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+        else if ((kw & 1) == 0)
+            hipLaunchKernelGGL((bgemm_small<2>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+        else
+            hipLaunchKernelGGL((bgemm_small<1>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
+        return hip_result(hipGetLastError());
+    }
     return launch_mfma<1, 1>(a, m, k, b, n, kw, ep, s);
 }
 

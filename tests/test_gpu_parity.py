@@ -81,6 +81,8 @@ def test_threshold_sign_maxpool(n, h, w, c, pool, use_flip):
 FC_SHAPES = [(1, 8, 32), (1, 33, 70), (3, 100, 96), (8, 40, 3136), (9, 130, 64), (64, 512, 512),
              (64, 10, 512), (200, 300, 1000), (129, 257, 4100), (256, 2048, 3136), (1, 1024, 8192),
              (130, 128, 128), (300, 10, 1024),
+             # small problems with K beyond one round of the K-split kernel (more than 32 units of 256 bits)
+             (40, 70, 20000), (33, 64, 16896), (256, 1024, 8192),
              # many whole tiles of the largest block shapes, 1 to 5 K chunks
              (2048, 1536, 512), (2048, 1536, 1536), (1920, 1664, 1024), (4096, 3072, 1024), (4096, 3072, 2560)]
 
