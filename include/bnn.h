@@ -244,6 +244,13 @@ int bnn_model_num_classes(const bnn_model *m);
  * TIMED synchronizes `stream`; GRAPH and STREAM only enqueue.  In GRAPH mode the chain is
  * captured the first time it is run with a given (input, logits, workspace) triple and
  * replayed afterwards; taps are ignored in GRAPH mode.
+ * Batch <= 8, three or more layers, the last two FC_BINARY and batch x classes <= 512: in
+ * GRAPH and STREAM mode the last layer (no step, hence linear in its input bits; Sec. II-A)
+ * has no launch of its own.  The first layer's launch zeroes `logits_dev` and the blocks of
+ * the layer before the last add their output word's share of every logit with integer
+ * atomics (exact in any order).  Results are those of TIMED mode, which keeps one launch per
+ * layer; `logits_dev` is written by more than one launch, so it must not alias the input,
+ * the workspace or a tap.
  * Errors: NULL, ALIGN, WORKSPACE, HIP.
  */
 bnn_status bnn_run_model(bnn_model *m, const int8_t *input_dev, int32_t *logits_dev,

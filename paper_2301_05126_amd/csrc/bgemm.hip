@@ -431,15 +431,32 @@ __global__ __launch_bounds__(256) void bgemm_small(const uint32_t *__restrict__ 
 // and streams their B rows with all loads of a K slice in flight at once.  Lanes stride K
 // (16 bytes per lane when VEC == 4), accumulate popcount(a ^ b), then a halving butterfly
 // reduces the 4 partial sums per lane over the 64 lanes with 2 + 1 + 4 shuffles per row.
-template <int MT, int VEC>
+//
+// TAIL: the layer after this one is the model's last, which has no step and is therefore linear
+// in this layer's output bits.  A block holds one whole 32-bit word of every output row, so it
+// adds that word's share of each logit, valid - 2 popcount((word ^ w) & mask), to the logits with
+// integer atomics (exact and independent of the order of arrival); the logits must be zero when
+// the launch starts.  One thread per (row, logit): M * n_out <= 512.
+template <int MT, int VEC, bool TAIL>
 __global__ __launch_bounds__(512) void bgemv_rows(const uint32_t *__restrict__ A,
                                                   const uint32_t *__restrict__ B, int M, int64_t N, int Kw,
-                                                  int K, EpiArgs ep)
+                                                  int K, EpiArgs ep, FcTailArgs tail)
 {
     __shared__ int xs[MT][32];
+    __shared__ uint32_t out_word[MT];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int64_t o_base = (int64_t)blockIdx.x * 32;
+
+    // this thread's word of the last layer's weights, on its way while the dot products run
+    uint32_t w_tail = 0;
+    int tail_r = 0, tail_j = 0;
+    const bool tail_on = TAIL && (int)threadIdx.x < M * tail.n_out;
+    if (tail_on) {
+        tail_r = (int)threadIdx.x / tail.n_out;
+        tail_j = (int)threadIdx.x - tail_r * tail.n_out;
+        w_tail = tail.w[(int64_t)tail_j * ((N + 31) >> 5) + blockIdx.x];
+    }
 
     int acc[MT][4];
 #pragma unroll
@@ -520,7 +537,20 @@ __global__ __launch_bounds__(512) void bgemv_rows(const uint32_t *__restrict__ A
             const unsigned long long mask = __ballot(bit);   // lanes 0-31: row r, 32-63: row r+1
             const unsigned word = (lane < 32) ? (unsigned)(mask & 0xffffffffull) : (unsigned)(mask >> 32);
             const int64_t nw = (N + 31) >> 5;
-            if (ol == 0 && r < M && r < MT) ep.packed[(int64_t)r * nw + blockIdx.x] = word;
+            if (ol == 0 && r < M && r < MT) {
+                ep.packed[(int64_t)r * nw + blockIdx.x] = word;
+                if (TAIL) out_word[r] = word;
+            }
+        }
+    }
+    if (TAIL) {
+        __syncthreads();
+        if (tail_on) {
+            const int64_t left = N - o_base;                 // output bits this block's word holds
+            const int valid = left < 32 ? (int)left : 32;
+            const uint32_t mask = valid < 32 ? ((1u << valid) - 1u) : 0xffffffffu;
+            const int part = valid - 2 * __builtin_popcount((out_word[tail_r] ^ w_tail) & mask);
+            atomicAdd(&tail.logits[(int64_t)tail_r * tail.n_out + tail_j], part);
         }
     }
 }
@@ -555,10 +585,11 @@ bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint3
     const int kw = (int)((k + 31) / 32);
     if (m <= 8) {
         dim3 grid((unsigned)ceil_div64(n, 32));
+        const FcTailArgs none = {nullptr, nullptr, 0};
         if ((kw & 3) == 0)
-            hipLaunchKernelGGL((bgemv_rows<8, 4>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep);
+            hipLaunchKernelGGL((bgemv_rows<8, 4, false>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, none);
         else
-            hipLaunchKernelGGL((bgemv_rows<8, 1>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep);
+            hipLaunchKernelGGL((bgemv_rows<8, 1, false>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, none);
         return hip_result(hipGetLastError());
     }
     // largest tile that still fills most of the 256 compute units
@@ -578,6 +609,25 @@ bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint3
         return hip_result(hipGetLastError());
     }
     return launch_mfma<1, 1>(a, m, k, b, n, kw, ep, s);
+}
+
+bool fc_binary_tail_qualifies(int64_t m, int64_t n_out)
+{
+    return m >= 1 && m <= FC_TAIL_MAX_ROWS && n_out >= 1 && m * n_out <= 512;
+}
+
+bnn_status launch_fc_binary_tail(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
+                                 const EpiArgs &ep, const FcTailArgs &tail, hipStream_t s)
+{
+    if (!fc_binary_tail_qualifies(m, tail.n_out) || !ep.packed || !tail.w || !tail.logits)
+        return BNN_ERR_UNSUPPORTED;
+    const int kw = (int)((k + 31) / 32);
+    dim3 grid((unsigned)ceil_div64(n, 32));
+    if ((kw & 3) == 0)
+        hipLaunchKernelGGL((bgemv_rows<8, 4, true>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, tail);
+    else
+        hipLaunchKernelGGL((bgemv_rows<8, 1, true>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, tail);
+    return hip_result(hipGetLastError());
 }
 
 }  // namespace bnn

@@ -110,8 +110,10 @@ bnn_status bnn_threshold_sign_maxpool(const int32_t *preact_dev, int n, int h, i
                                          (hipStream_t)stream);
 }
 
-bnn_status bnn_fc_binary(const uint32_t *a_dev, int64_t m, int64_t k, const uint32_t *b_dev, int64_t n,
-                         const bnn_epilogue *ep, int32_t *c_out_dev, uint32_t *packed_out_dev, void *stream)
+// bnn_fc_binary; with `tail` (batch <= 8 only) the model's last layer is folded into this launch.
+static bnn_status fc_binary_checked(const uint32_t *a_dev, int64_t m, int64_t k, const uint32_t *b_dev, int64_t n,
+                                    const bnn_epilogue *ep, int32_t *c_out_dev, uint32_t *packed_out_dev,
+                                    const FcTailArgs *tail, void *stream)
 {
     if (!a_dev || !b_dev) return BNN_ERR_NULL;
     if (m < 0 || k <= 0 || n <= 0) return BNN_ERR_SHAPE;
@@ -125,7 +127,14 @@ bnn_status bnn_fc_binary(const uint32_t *a_dev, int64_t m, int64_t k, const uint
     if (m > 8 && k > FC_MFMA_MAX_K) return BNN_ERR_UNSUPPORTED;
     const int64_t tiles = ceil_div64(m, 128) * ceil_div64(n, 128);
     if (tiles > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+    if (tail) return launch_fc_binary_tail(a_dev, m, k, b_dev, n, ea, *tail, (hipStream_t)stream);
     return launch_fc_binary(a_dev, m, k, b_dev, n, ea, (hipStream_t)stream);
+}
+
+bnn_status bnn_fc_binary(const uint32_t *a_dev, int64_t m, int64_t k, const uint32_t *b_dev, int64_t n,
+                         const bnn_epilogue *ep, int32_t *c_out_dev, uint32_t *packed_out_dev, void *stream)
+{
+    return fc_binary_checked(a_dev, m, k, b_dev, n, ep, c_out_dev, packed_out_dev, nullptr, stream);
 }
 
 bnn_status bnn_conv_binary(const uint32_t *in_dev, int n, int h, int w, int c_in, const uint32_t *w_dev,
@@ -138,9 +147,11 @@ bnn_status bnn_conv_binary(const uint32_t *in_dev, int n, int h, int w, int c_in
     return launch_conv_binary(in_dev, n, h, w, c_in, w_dev, c_out, ea, (hipStream_t)stream);
 }
 
-bnn_status bnn_conv_first_int8(const int8_t *in_dev, int n, int h, int w, int c_in, const int8_t *w_dev,
-                               int c_out, int kh, int kw, int pad, int pad_value, const bnn_epilogue *ep,
-                               int32_t *preact_out_dev, uint32_t *packed_out_dev, void *stream)
+// bnn_conv_first_int8; `clr` names words that the launch also sets to zero (count 0: none).
+static bnn_status conv_first_int8_checked(const int8_t *in_dev, int n, int h, int w, int c_in, const int8_t *w_dev,
+                                          int c_out, int kh, int kw, int pad, int pad_value,
+                                          const bnn_epilogue *ep, int32_t *preact_out_dev,
+                                          uint32_t *packed_out_dev, const ClearArgs &clr, void *stream)
 {
     if (!in_dev || !w_dev) return BNN_ERR_NULL;
     if (n < 0 || h <= 0 || w <= 0 || c_in <= 0 || c_out <= 0 || kh <= 0 || kw <= 0 || pad < 0)
@@ -154,8 +165,17 @@ bnn_status bnn_conv_first_int8(const int8_t *in_dev, int n, int h, int w, int c_
     bnn_status st = check_epilogue(ep, preact_out_dev, packed_out_dev, (int)ho, (int)wo, true, &ea);
     if (st != BNN_OK) return st;
     if (!aligned16(in_dev) || !aligned16(w_dev)) return BNN_ERR_ALIGN;
-    return launch_conv_first_int8(in_dev, n, h, w, c_in, w_dev, c_out, kh, kw, pad, pad_value, ea,
+    return launch_conv_first_int8(in_dev, n, h, w, c_in, w_dev, c_out, kh, kw, pad, pad_value, ea, clr,
                                   (hipStream_t)stream);
+}
+
+bnn_status bnn_conv_first_int8(const int8_t *in_dev, int n, int h, int w, int c_in, const int8_t *w_dev,
+                               int c_out, int kh, int kw, int pad, int pad_value, const bnn_epilogue *ep,
+                               int32_t *preact_out_dev, uint32_t *packed_out_dev, void *stream)
+{
+    const ClearArgs none = {nullptr, 0};
+    return conv_first_int8_checked(in_dev, n, h, w, c_in, w_dev, c_out, kh, kw, pad, pad_value, ep,
+                                   preact_out_dev, packed_out_dev, none, stream);
 }
 
 /* ------------------------------------------------------------------ whole model ----- */
@@ -168,6 +188,10 @@ struct bnn_model {
     std::vector<int64_t> macs, bytes_alg;
     size_t buf_bytes;          // one ping-pong buffer (256-byte multiple)
     int n_classes;
+    // batch <= 8 and the last two layers fully connected: outside TIMED mode the last layer (no
+    // step, so linear in its input bits) runs inside the launch of the layer before it, which adds
+    // each output word's share to the logits; the first layer's launch zeroes them
+    bool fold_last;
     // captured graph (GRAPH mode)
     hipGraph_t graph;
     hipGraphExec_t graph_exec;
@@ -309,6 +333,8 @@ bnn_status bnn_model_create(const bnn_layer_desc *layers, int n_layers, int batc
     if (st != BNN_OK) { delete m; return st; }
     m->buf_bytes = round_up(m->buf_bytes ? m->buf_bytes : 16, 256);
     m->n_classes = m->layers.back().c_out;
+    m->fold_last = n_layers >= 3 && m->layers[n_layers - 2].kind == BNN_LAYER_FC_BINARY &&
+                   fc_binary_tail_qualifies(batch, m->n_classes);
     *out = m;
     return BNN_OK;
 }
@@ -319,28 +345,39 @@ int bnn_model_num_classes(const bnn_model *m) { return m ? m->n_classes : 0; }
 
 // Enqueue layer l: reads `src` (int8 image for l == 0, packed otherwise), writes `dst`
 // (packed) or the logits.
+// fold: the last layer rides on the launch of the one before it (see bnn_model::fold_last).
 static bnn_status enqueue_layer(bnn_model *m, int l, const void *src, void *dst, int32_t *logits,
-                                bool taps, hipStream_t s)
+                                bool taps, bool fold, hipStream_t s)
 {
     const bnn_layer_desc &L = m->layers[l];
+    const int nl = (int)m->layers.size();
     bnn_epilogue ep;
     ep.thr = L.thr_dev; ep.flip = L.flip_dev; ep.pool = L.has_step ? L.pool : 1;
     ep.pool_first = L.pool_first;
     const bnn_epilogue *epp = L.has_step ? &ep : nullptr;
     int32_t *raw = L.has_step ? (taps ? L.preact_tap_dev : nullptr) : logits;
     uint32_t *packed = L.has_step ? (uint32_t *)dst : nullptr;
-    bnn_status st;
+    bnn_status st = BNN_OK;
     switch (L.kind) {
-    case BNN_LAYER_CONV_FIRST_INT8:
-        st = bnn_conv_first_int8((const int8_t *)src, m->batch, m->h_in[l], m->w_in[l], L.c_in,
-                                 (const int8_t *)L.weights_dev, L.c_out, L.kh, L.kw, L.pad, L.pad_value, epp,
-                                 raw, packed, s);
+    case BNN_LAYER_CONV_FIRST_INT8: {
+        const ClearArgs clr = {fold ? logits : nullptr, fold ? m->batch * m->n_classes : 0};
+        st = conv_first_int8_checked((const int8_t *)src, m->batch, m->h_in[l], m->w_in[l], L.c_in,
+                                     (const int8_t *)L.weights_dev, L.c_out, L.kh, L.kw, L.pad, L.pad_value,
+                                     epp, raw, packed, clr, s);
         break;
+    }
     case BNN_LAYER_CONV_BINARY:
         st = bnn_conv_binary((const uint32_t *)src, m->batch, m->h_in[l], m->w_in[l], L.c_in,
                              (const uint32_t *)L.weights_dev, L.c_out, epp, raw, packed, s);
         break;
     default:
+        if (fold && l == nl - 1) break;             // done by the launch of layer nl - 2
+        if (fold && l == nl - 2) {
+            const FcTailArgs tail = {(const uint32_t *)m->layers[nl - 1].weights_dev, logits, m->n_classes};
+            st = fc_binary_checked((const uint32_t *)src, m->batch, L.c_in, (const uint32_t *)L.weights_dev,
+                                   L.c_out, epp, raw, packed, &tail, s);
+            break;
+        }
         st = bnn_fc_binary((const uint32_t *)src, m->batch, L.c_in, (const uint32_t *)L.weights_dev, L.c_out,
                            epp, raw, packed, s);
         break;
@@ -370,7 +407,7 @@ static bnn_status enqueue_chain(bnn_model *m, const int8_t *input, int32_t *logi
             if (e != BNN_OK) return e;
         }
         void *dst = buf[l & 1];
-        bnn_status st = enqueue_layer(m, l, src, dst, logits, taps, s);
+        bnn_status st = enqueue_layer(m, l, src, dst, logits, taps, !timed && m->fold_last, s);
         if (st != BNN_OK) return st;
         src = dst;
     }

@@ -21,6 +21,22 @@ struct EpiArgs {
     int pool_first;        // 1: max of the int32 window first, then the step
 };
 
+// The model's last layer (fully connected, no step) folded into the layer that produces its
+// input: `w` = that last layer's packed weights [n_out][ceil(n/32)], `logits` = [m][n_out] int32,
+// zero when the producing launch starts; every block of the producer adds its share.
+struct FcTailArgs {
+    const uint32_t *w;
+    int32_t *logits;
+    int n_out;
+};
+
+// A few int32 words that a first-layer launch sets to zero on the side (its first block does it):
+// the accumulator that a later launch of the same chain adds into.  count == 0: nothing.
+struct ClearArgs {
+    int32_t *ptr;
+    int count;
+};
+
 // Records a HIP error for bnn_last_hip_error() and returns BNN_ERR_HIP, or BNN_OK.
 bnn_status hip_result(hipError_t e);
 
@@ -33,11 +49,17 @@ bnn_status launch_threshold_sign_maxpool(const int32_t *x, int n, int h, int w, 
                                          int pool_first, uint32_t *out, hipStream_t s);
 bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
                             const EpiArgs &ep, hipStream_t s);
+// launch_fc_binary for m <= FC_TAIL_MAX_ROWS rows with the following (last, step-less) layer folded
+// in; fc_binary_tail_qualifies says whether (m, n_out of the last layer) can take this path.
+constexpr int FC_TAIL_MAX_ROWS = 8;
+bool fc_binary_tail_qualifies(int64_t m, int64_t n_out);
+bnn_status launch_fc_binary_tail(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
+                                 const EpiArgs &ep, const FcTailArgs &tail, hipStream_t s);
 bnn_status launch_conv_binary(const uint32_t *in, int n, int h, int w, int c_in,
                               const uint32_t *wt, int c_out, const EpiArgs &ep, hipStream_t s);
 bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_in,
                                   const int8_t *wt, int c_out, int kh, int kw, int pad,
-                                  int pad_value, const EpiArgs &ep, hipStream_t s);
+                                  int pad_value, const EpiArgs &ep, const ClearArgs &clear, hipStream_t s);
 
 // The small-problem kernel of launch_conv_binary; BNN_ERR_UNSUPPORTED if the layer does not qualify.
 bnn_status launch_conv_binary_small(const uint32_t *in, int n, int h, int w, int c_in,

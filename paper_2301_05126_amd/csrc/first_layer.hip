@@ -35,11 +35,19 @@ struct FirstGeom {
     int ho, wo, pool, k, k4;
 };
 
+// The launch's first block zeroes the few words a later launch of the same chain accumulates into.
+__device__ __forceinline__ void clear_words(const ClearArgs &c)
+{
+    if (c.count > 0 && blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = threadIdx.x; i < c.count; i += 256) c.ptr[i] = 0;
+}
+
 __global__ __launch_bounds__(256) void conv_first_kernel(const int8_t *__restrict__ in,
                                                          const int8_t *__restrict__ wt, FirstGeom g,
-                                                         EpiArgs ep)
+                                                         EpiArgs ep, ClearArgs clr)
 {
     __shared__ int W4[K4C][32];
+    clear_words(clr);
 
     const int t = threadIdx.x;
     const int cg = blockIdx.y;                 // group of 32 output channels
@@ -181,9 +189,11 @@ __device__ __forceinline__ int div_magic(int n, unsigned mg) { return mg ? (int)
 // immediate, and the pixel-tile and channel-group loops are straight-line code.
 template <int NG, bool PIPE, int NS>
 __global__ __launch_bounds__(256, NS > 0 ? 4 : 3) void conv_first_mfma(const int8_t *__restrict__ in,
-                                                       const int8_t *__restrict__ wt, FirstGeomM g, EpiArgs ep)
+                                                       const int8_t *__restrict__ wt, FirstGeomM g, EpiArgs ep,
+                                                       ClearArgs clr)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    clear_words(clr);
     constexpr bool FAST = NS > 0;
     constexpr int NSA = FAST ? NS : 1;
     const int ws = FAST ? NS * 32 + 16 : g.kp + 16;             // weight row stride in bytes
@@ -498,9 +508,10 @@ struct FirstGeomI {
 
 template <int NG, int NU>
 __global__ __launch_bounds__(256, 4) void conv_first_img(const int8_t *__restrict__ in, const int8_t *__restrict__ wt,
-                                                         FirstGeomI g, EpiArgs ep)
+                                                         FirstGeomI g, EpiArgs ep, ClearArgs clr)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    clear_words(clr);
     constexpr int NS = 2, TN = 2, BW = 2 * NG, WS = NS * 32 + 16;
     unsigned char *Wl = smem;                                                    // [64*NG][WS]
     uint32_t *Ol = reinterpret_cast<uint32_t *>(smem + 64 * NG * WS);            // [2][256][BW]
@@ -736,8 +747,9 @@ __global__ __launch_bounds__(256, 4) void conv_first_img(const int8_t *__restric
 // 1x1, pad 0, c_in % 16 == 0: int8 GEMM  X[m][o] = sum_c A[m][c] * W[o][c];  m = pixel index.
 // Block = 2 x 2 waves, one 32 x 32 tile each; operands are 16-byte global loads.
 __global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ A, const int8_t *__restrict__ Wt,
-                                                     int64_t M, int N, int K, EpiArgs ep)
+                                                     int64_t M, int N, int K, EpiArgs ep, ClearArgs clr)
 {
+    clear_words(clr);
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
     const int l32 = lane & 31, half = lane >> 5;
@@ -785,7 +797,8 @@ __global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ 
 }
 
 template <int NG>
-bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, const EpiArgs &ep, hipStream_t s)
+bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, const EpiArgs &ep,
+                             const ClearArgs &clr, hipStream_t s)
 {
     g.n_co_tiles = (g.c_out + 64 * NG - 1) / (64 * NG);
     // pipelined patch: four bytes per thread, each addressed by a 32-bit offset from the tile origin
@@ -810,13 +823,13 @@ bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, 
         g.mg_ty = magic_floor(g.tiles_y);
     }
     if (fast && ns == 1)
-        hipLaunchKernelGGL((conv_first_mfma<NG, true, 1>), grid, dim3(256), smem, s, in, wt, g, ep);
+        hipLaunchKernelGGL((conv_first_mfma<NG, true, 1>), grid, dim3(256), smem, s, in, wt, g, ep, clr);
     else if (fast)
-        hipLaunchKernelGGL((conv_first_mfma<NG, true, 2>), grid, dim3(256), smem, s, in, wt, g, ep);
+        hipLaunchKernelGGL((conv_first_mfma<NG, true, 2>), grid, dim3(256), smem, s, in, wt, g, ep, clr);
     else if (pipe)
-        hipLaunchKernelGGL((conv_first_mfma<NG, true, 0>), grid, dim3(256), smem, s, in, wt, g, ep);
+        hipLaunchKernelGGL((conv_first_mfma<NG, true, 0>), grid, dim3(256), smem, s, in, wt, g, ep, clr);
     else
-        hipLaunchKernelGGL((conv_first_mfma<NG, false, 0>), grid, dim3(256), smem, s, in, wt, g, ep);
+        hipLaunchKernelGGL((conv_first_mfma<NG, false, 0>), grid, dim3(256), smem, s, in, wt, g, ep, clr);
     return hip_result(hipGetLastError());
 }
 
@@ -824,7 +837,7 @@ bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, 
 // of two that a 256-pixel tile spans, image groups of at most 8 KB.  BNN_ERR_UNSUPPORTED otherwise.
 template <int NG>
 bnn_status launch_first_img(const int8_t *in, const int8_t *wt, int n, int h, int w, int c_in, int c_out,
-                            int pad_value, const EpiArgs &ep, hipStream_t s)
+                            int pad_value, const EpiArgs &ep, const ClearArgs &clr, hipStream_t s)
 {
     // a 256-pixel tile spans the whole image width (a power of two, 2 .. 128); it takes 256 / w rows
     // of one image, or whole images when they have fewer than 256 pixels (height a power of two then)
@@ -867,9 +880,9 @@ bnn_status launch_first_img(const int8_t *in, const int8_t *wt, int n, int h, in
     const dim3 grid((unsigned)(units < 1024 ? units : 1024), (unsigned)n_co_tiles);
     const int group_bytes = g.ni * g.img_bytes;
     if (group_bytes <= 4096)
-        hipLaunchKernelGGL((conv_first_img<NG, 1>), grid, dim3(256), smem, s, in, wt, g, ep);
+        hipLaunchKernelGGL((conv_first_img<NG, 1>), grid, dim3(256), smem, s, in, wt, g, ep, clr);
     else
-        hipLaunchKernelGGL((conv_first_img<NG, 2>), grid, dim3(256), smem, s, in, wt, g, ep);
+        hipLaunchKernelGGL((conv_first_img<NG, 2>), grid, dim3(256), smem, s, in, wt, g, ep, clr);
     return hip_result(hipGetLastError());
 }
 
@@ -877,7 +890,7 @@ bnn_status launch_first_img(const int8_t *in, const int8_t *wt, int n, int h, in
 
 bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_in, const int8_t *wt,
                                   int c_out, int kh, int kw, int pad, int pad_value, const EpiArgs &ep,
-                                  hipStream_t s)
+                                  const ClearArgs &clr, hipStream_t s)
 {
     if (n == 0) return BNN_OK;
     const int ho_ = h + 2 * pad - kh + 1, wo_ = w + 2 * pad - kw + 1;
@@ -887,7 +900,7 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
         const int64_t M = (int64_t)n * h * w;
         const int64_t blocks = ceil_div64(M, 64) * ceil_div64(c_out, 64);
         if (blocks <= 0x7fffffffLL) {
-            hipLaunchKernelGGL(fc_first_mfma, dim3((unsigned)blocks), dim3(256), 0, s, in, wt, M, c_out, c_in, ep);
+            hipLaunchKernelGGL(fc_first_mfma, dim3((unsigned)blocks), dim3(256), 0, s, in, wt, M, c_out, c_in, ep, clr);
             return hip_result(hipGetLastError());
         }
     }
@@ -896,8 +909,8 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
         const TileShape ts = make_tile_shape(ho_, wo_, 256);
         const int64_t ptiles = (int64_t)ts.tiles_x * ts.tiles_y * ((n + ts.ni - 1) / ts.ni);
         const bool two_groups = c_out > 64 && ptiles * ((c_out + 127) / 128) >= 256;
-        const bnn_status st = two_groups ? launch_first_img<2>(in, wt, n, h, w, c_in, c_out, pad_value, ep, s)
-                                         : launch_first_img<1>(in, wt, n, h, w, c_in, c_out, pad_value, ep, s);
+        const bnn_status st = two_groups ? launch_first_img<2>(in, wt, n, h, w, c_in, c_out, pad_value, ep, clr, s)
+                                         : launch_first_img<1>(in, wt, n, h, w, c_in, c_out, pad_value, ep, clr, s);
         if (st != BNN_ERR_UNSUPPORTED) return st;
     }
     // small kernels: patch + weights in LDS, matrix cores
@@ -924,8 +937,8 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
             // the chip (small batches) one group per block doubles the blocks instead
             const int64_t ptiles = (int64_t)g.tiles_x * g.tiles_y * ((n + g.ni - 1) / g.ni);
             const bool two_groups = c_out > 64 && ptiles * ((c_out + 127) / 128) >= 256;
-            const bnn_status st = two_groups ? launch_first_mfma<2>(in, wt, g, ep, s)
-                                             : launch_first_mfma<1>(in, wt, g, ep, s);
+            const bnn_status st = two_groups ? launch_first_mfma<2>(in, wt, g, ep, clr, s)
+                                             : launch_first_mfma<1>(in, wt, g, ep, clr, s);
             if (st != BNN_ERR_UNSUPPORTED) return st;
         }
     }
@@ -941,7 +954,7 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
     const int64_t bx = (total + 255) / 256;
     const int by = (c_out + 31) / 32;
     if (bx > 0x7fffffffLL || by > 65535) return BNN_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(conv_first_kernel, dim3((unsigned)bx, (unsigned)by), dim3(256), 0, s, in, wt, g, ep);
+    hipLaunchKernelGGL(conv_first_kernel, dim3((unsigned)bx, (unsigned)by), dim3(256), 0, s, in, wt, g, ep, clr);
     return hip_result(hipGetLastError());
 }
 
