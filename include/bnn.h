@@ -244,9 +244,11 @@ int bnn_model_num_classes(const bnn_model *m);
  * TIMED synchronizes `stream`; GRAPH and STREAM only enqueue.  In GRAPH mode the chain is
  * captured the first time it is run with a given (input, logits, workspace) triple and
  * replayed afterwards; taps are ignored in GRAPH mode.
- * Batch <= 8, three or more layers, the last two FC_BINARY and batch x classes <= 512: in
- * GRAPH and STREAM mode the last layer (no step, hence linear in its input bits; Sec. II-A)
- * has no launch of its own.  The first layer's launch zeroes `logits_dev` and the blocks of
+ * Small batches (three or more layers, the last two FC_BINARY; batch <= 8 with batch x
+ * classes <= 512 and a last hidden layer of at most 8192 outputs, or a larger batch whose last
+ * hidden layer has at most 1024 outputs, is too small for the 64 x 64 GEMM tiles and feeds at
+ * most 16 classes): in GRAPH and STREAM mode the last layer (no step, hence
+ * linear in its input bits; Sec. II-A) has no launch of its own.  The first layer's launch zeroes `logits_dev` and the blocks of
  * the layer before the last add their output word's share of every logit with integer
  * atomics (exact in any order).  Results are those of TIMED mode, which keeps one launch per
  * layer; `logits_dev` is written by more than one launch, so it must not alias the input,

@@ -347,18 +347,32 @@ __global__ __launch_bounds__(256, 1) void bgemm_mfma(const uint32_t *__restrict_
 // MFMAs); the partial sums meet in LDS and wave 0 runs the epilogue.  Latency, not throughput:
 // with a quarter of K per wave and four times the blocks, a batch-256 FC layer of K = 8192 takes
 // half the time of the 64 x 64 tile.
-template <int VEC>
+//
+// TAIL (see bgemv_rows): the block's 32 output words, one per row, each give their share of at
+// most 16 logits per row; thread t adds those of row t % 32 and classes t / 32 and t / 32 + 8.
+template <int VEC, bool TAIL>
 __global__ __launch_bounds__(256) void bgemm_small(const uint32_t *__restrict__ A, const uint32_t *__restrict__ B,
-                                                   int64_t M, int64_t N, int Kw, int K, int nbn, EpiArgs ep)
+                                                   int64_t M, int64_t N, int Kw, int K, int nbn, EpiArgs ep,
+                                                   FcTailArgs tail)
 {
     constexpr int UR = 8;                   // units per wave and round
     __shared__ float red[3][16][64];        // partial sums of waves 1..3
+    __shared__ uint32_t out_word[32];
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int64_t m0 = (int64_t)(blockIdx.x / nbn) * 32;
     const int64_t n0 = (int64_t)(blockIdx.x % nbn) * 32;
     const int units = (Kw + 7) >> 3;
+
+    uint32_t w_tail[2] = {0u, 0u};          // on their way while the dot products run
+    if (TAIL) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = (t >> 5) + 8 * i;
+            if (j < tail.n_out) w_tail[i] = tail.w[(int64_t)j * ((N + 31) >> 5) + (n0 >> 5)];
+        }
+    }
 
     uint32_t sgn = 0x88888888u, one = 0x22222222u;
     asm volatile("" : "+s"(sgn));
@@ -392,37 +406,54 @@ __global__ __launch_bounds__(256) void bgemm_small(const uint32_t *__restrict__ 
         for (int r = 0; r < 16; ++r) red[wave - 1][r][lane] = acc[r];
     }
     __syncthreads();
-    if (wave != 0) return;
+    if (wave == 0) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
+        for (int r = 0; r < 16; ++r)
 #pragma unroll
-        for (int v = 0; v < 3; ++v) acc[r] += red[v][r][lane];      // small integers: exact in any order
+            for (int v = 0; v < 3; ++v) acc[r] += red[v][r][lane];      // small integers: exact in any order
 
-    // ---- epilogue of one 32 x 32 tile: register r of lane (l32, half) is row 8(r/4) + 4*half + r%4, column l32
-    const int corr = units * 8 * 32 - K;        // zero words and tail bits all counted as +1
-    const int64_t rbase = m0 + half * 4, col = n0 + l32;
-    const bool cok = col < N;
-    if (ep.preact) {
+        // ---- epilogue of one 32 x 32 tile: register r of lane (l32, half) is row 8(r/4) + 4*half + r%4, column l32
+        const int corr = units * 8 * 32 - K;        // zero words and tail bits all counted as +1
+        const int64_t rbase = m0 + half * 4, col = n0 + l32;
+        const bool cok = col < N;
+        if (ep.preact) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t row = rbase + (r >> 2) * 8 + (r & 3);
-            if (row < M && cok) ep.preact[row * N + col] = (int)acc[r] - corr;
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = rbase + (r >> 2) * 8 + (r & 3);
+                if (row < M && cok) ep.preact[row * N + col] = (int)acc[r] - corr;
+            }
+        }
+        if (ep.packed) {
+            const int64_t nw = (N + 31) >> 5;
+            const int thr = cok ? ep.thr[col] : 0;
+            const bool flip = cok && ep.flip && ep.flip[col];
+            unsigned mine = 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int x = (int)acc[r] - corr;
+                const unsigned long long mask = __ballot(cok && ((x > thr) != flip));
+                const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
+                if (l32 == r) mine = word;          // lane r of each half keeps the word of register r
+            }
+            const int64_t row = rbase + (l32 >> 2) * 8 + (l32 & 3);
+            if (l32 < 16 && row < M) ep.packed[row * nw + (n0 >> 5)] = mine;
+            if (TAIL && l32 < 16) out_word[half * 4 + (l32 >> 2) * 8 + (l32 & 3)] = mine;
         }
     }
-    if (ep.packed) {
-        const int64_t nw = (N + 31) >> 5;
-        const int thr = cok ? ep.thr[col] : 0;
-        const bool flip = cok && ep.flip && ep.flip[col];
-        unsigned mine = 0;
+    if (TAIL) {
+        __syncthreads();
+        const int r = t & 31;
+        const int64_t left = N - n0;                        // output bits the block's words hold
+        const int valid = left < 32 ? (int)left : 32;
+        const uint32_t mask = valid < 32 ? ((1u << valid) - 1u) : 0xffffffffu;
+        const uint32_t wd = out_word[r];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int x = (int)acc[r] - corr;
-            const unsigned long long mask = __ballot(cok && ((x > thr) != flip));
-            const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
-            if (l32 == r) mine = word;          // lane r of each half keeps the word of register r
+        for (int i = 0; i < 2; ++i) {
+            const int j = (t >> 5) + 8 * i;
+            if (j < tail.n_out && m0 + r < M)
+                atomicAdd(&tail.logits[(m0 + r) * tail.n_out + j],
+                          valid - 2 * __builtin_popcount((wd ^ w_tail[i]) & mask));
         }
-        const int64_t row = rbase + (l32 >> 2) * 8 + (l32 & 3);
-        if (l32 < 16 && row < M) ep.packed[row * nw + (n0 >> 5)] = mine;
     }
 }
 
@@ -576,6 +607,27 @@ bnn_status launch_mfma(const uint32_t *a, int64_t m, int64_t k, const uint32_t *
     return hip_result(hipGetLastError());
 }
 
+// more than 8 rows, too few tiles for any of the three block tiles
+bool fc_takes_small_kernel(int64_t m, int64_t n)
+{
+    return m > 8 && ceil_div64(m, 64) * ceil_div64(n, 64) < 192;
+}
+
+template <bool TAIL>
+bnn_status launch_small(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n, int kw,
+                        const EpiArgs &ep, const FcTailArgs &tail, hipStream_t s)
+{
+    const int nbn = (int)ceil_div64(n, 32);
+    const dim3 grid((unsigned)(nbn * ceil_div64(m, 32)));
+    if ((kw & 3) == 0)
+        hipLaunchKernelGGL((bgemm_small<4, TAIL>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep, tail);
+    else if ((kw & 1) == 0)
+        hipLaunchKernelGGL((bgemm_small<2, TAIL>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep, tail);
+    else
+        hipLaunchKernelGGL((bgemm_small<1, TAIL>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep, tail);
+    return hip_result(hipGetLastError());
+}
+
 }  // namespace
 
 bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
@@ -597,31 +649,31 @@ bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint3
     if (ceil_div64(m, 256) * ceil_div64(n, 256) >= want) return launch_mfma<4, 4>(a, m, k, b, n, kw, ep, s);
     if (ceil_div64(m, 128) * ceil_div64(n, 128) >= want) return launch_mfma<2, 2>(a, m, k, b, n, kw, ep, s);
     // fewer than that many 64 x 64 tiles: 32 x 32 tiles with K split over the block's waves
-    if (ceil_div64(m, 64) * ceil_div64(n, 64) < want) {
-        const int nbn = (int)ceil_div64(n, 32);
-        const dim3 grid((unsigned)(nbn * ceil_div64(m, 32)));
-        if ((kw & 3) == 0)
-            hipLaunchKernelGGL((bgemm_small<4>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
-        else if ((kw & 1) == 0)
-            hipLaunchKernelGGL((bgemm_small<2>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
-        else
-            hipLaunchKernelGGL((bgemm_small<1>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, nbn, ep);
-        return hip_result(hipGetLastError());
+    if (fc_takes_small_kernel(m, n)) {
+        const FcTailArgs none = {nullptr, nullptr, 0};
+        return launch_small<false>(a, m, k, b, n, kw, ep, none, s);
     }
     return launch_mfma<1, 1>(a, m, k, b, n, kw, ep, s);
 }
 
-bool fc_binary_tail_qualifies(int64_t m, int64_t n_out)
+bool fc_binary_tail_qualifies(int64_t m, int64_t n, int64_t n_out)
 {
-    return m >= 1 && m <= FC_TAIL_MAX_ROWS && n_out >= 1 && m * n_out <= 512;
+    if (m < 1 || n_out < 1) return false;
+    // Every logit receives one atomic per 32 outputs of this layer, and additions to one address
+    // queue up behind each other: beyond these widths (measured: hidden layers of 512 .. 32768
+    // outputs, with and without the tail) a launch of its own for the last layer is faster.
+    if (m <= 8) return m * n_out <= 512 && n <= 8192;       // bgemv_rows: one thread per (row, class)
+    return fc_takes_small_kernel(m, n) && n_out <= 16 &&    // bgemm_small: two classes per thread
+           n <= 1024 && m * n_out <= FC_TAIL_MAX_LOGITS;
 }
 
 bnn_status launch_fc_binary_tail(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
                                  const EpiArgs &ep, const FcTailArgs &tail, hipStream_t s)
 {
-    if (!fc_binary_tail_qualifies(m, tail.n_out) || !ep.packed || !tail.w || !tail.logits)
+    if (!fc_binary_tail_qualifies(m, n, tail.n_out) || !ep.packed || !tail.w || !tail.logits)
         return BNN_ERR_UNSUPPORTED;
     const int kw = (int)((k + 31) / 32);
+    if (m > 8) return launch_small<true>(a, m, k, b, n, kw, ep, tail, s);
     dim3 grid((unsigned)ceil_div64(n, 32));
     if ((kw & 3) == 0)
         hipLaunchKernelGGL((bgemv_rows<8, 4, true>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, tail);

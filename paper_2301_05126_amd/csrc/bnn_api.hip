@@ -110,7 +110,7 @@ bnn_status bnn_threshold_sign_maxpool(const int32_t *preact_dev, int n, int h, i
                                          (hipStream_t)stream);
 }
 
-// bnn_fc_binary; with `tail` (batch <= 8 only) the model's last layer is folded into this launch.
+// bnn_fc_binary; with `tail` (small batches only) the model's last layer is folded into this launch.
 static bnn_status fc_binary_checked(const uint32_t *a_dev, int64_t m, int64_t k, const uint32_t *b_dev, int64_t n,
                                     const bnn_epilogue *ep, int32_t *c_out_dev, uint32_t *packed_out_dev,
                                     const FcTailArgs *tail, void *stream)
@@ -188,9 +188,10 @@ struct bnn_model {
     std::vector<int64_t> macs, bytes_alg;
     size_t buf_bytes;          // one ping-pong buffer (256-byte multiple)
     int n_classes;
-    // batch <= 8 and the last two layers fully connected: outside TIMED mode the last layer (no
-    // step, so linear in its input bits) runs inside the launch of the layer before it, which adds
-    // each output word's share to the logits; the first layer's launch zeroes them
+    // the last two layers fully connected and the one before the last on bgemv_rows or bgemm_small
+    // (small batches): outside TIMED mode the last layer (no step, so linear in its input bits)
+    // runs inside the launch of the layer before it, which adds each output word's share to the
+    // logits; the first layer's launch zeroes them
     bool fold_last;
     // captured graph (GRAPH mode)
     hipGraph_t graph;
@@ -334,7 +335,7 @@ bnn_status bnn_model_create(const bnn_layer_desc *layers, int n_layers, int batc
     m->buf_bytes = round_up(m->buf_bytes ? m->buf_bytes : 16, 256);
     m->n_classes = m->layers.back().c_out;
     m->fold_last = n_layers >= 3 && m->layers[n_layers - 2].kind == BNN_LAYER_FC_BINARY &&
-                   fc_binary_tail_qualifies(batch, m->n_classes);
+                   fc_binary_tail_qualifies(batch, m->layers[n_layers - 2].c_out, m->n_classes);
     *out = m;
     return BNN_OK;
 }

@@ -30,8 +30,9 @@ struct FcTailArgs {
     int n_out;
 };
 
-// A few int32 words that a first-layer launch sets to zero on the side (its first block does it):
-// the accumulator that a later launch of the same chain adds into.  count == 0: nothing.
+// A few int32 words that a first-layer launch sets to zero on the side (its blocks with
+// blockIdx.y == 0 share them): the accumulator that a later launch of the same chain adds into.
+// count == 0: nothing.
 struct ClearArgs {
     int32_t *ptr;
     int count;
@@ -49,10 +50,11 @@ bnn_status launch_threshold_sign_maxpool(const int32_t *x, int n, int h, int w, 
                                          int pool_first, uint32_t *out, hipStream_t s);
 bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
                             const EpiArgs &ep, hipStream_t s);
-// launch_fc_binary for m <= FC_TAIL_MAX_ROWS rows with the following (last, step-less) layer folded
-// in; fc_binary_tail_qualifies says whether (m, n_out of the last layer) can take this path.
-constexpr int FC_TAIL_MAX_ROWS = 8;
-bool fc_binary_tail_qualifies(int64_t m, int64_t n_out);
+// launch_fc_binary with the following (last, step-less) layer of n_out classes folded in, for the
+// shapes that run on bgemv_rows or bgemm_small; fc_binary_tail_qualifies says which those are.
+// The logits (m x n_out <= FC_TAIL_MAX_LOGITS words) are zeroed on the side by an earlier launch.
+constexpr int64_t FC_TAIL_MAX_LOGITS = 1 << 16;
+bool fc_binary_tail_qualifies(int64_t m, int64_t n, int64_t n_out);
 bnn_status launch_fc_binary_tail(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
                                  const EpiArgs &ep, const FcTailArgs &tail, hipStream_t s);
 bnn_status launch_conv_binary(const uint32_t *in, int n, int h, int w, int c_in,

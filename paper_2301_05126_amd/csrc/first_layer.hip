@@ -35,11 +35,11 @@ struct FirstGeom {
     int ho, wo, pool, k, k4;
 };
 
-// The launch's first block zeroes the few words a later launch of the same chain accumulates into.
+// The launch's blocks zero, between them, the words a later launch of the same chain accumulates into.
 __device__ __forceinline__ void clear_words(const ClearArgs &c)
 {
-    if (c.count > 0 && blockIdx.x == 0 && blockIdx.y == 0)
-        for (int i = threadIdx.x; i < c.count; i += 256) c.ptr[i] = 0;
+    if (c.count > 0 && blockIdx.y == 0)
+        for (int i = blockIdx.x * 256 + threadIdx.x; i < c.count; i += gridDim.x * 256) c.ptr[i] = 0;
 }
 
 __global__ __launch_bounds__(256) void conv_first_kernel(const int8_t *__restrict__ in,

@@ -1,6 +1,7 @@
-"""Models at batch <= 8 whose last two layers are fully connected: outside TIMED mode the last
-layer (no step) runs inside the launch of the layer before it, as integer atomic additions into
-logits that the first layer's launch has zeroed.  Logits and every layer's outputs against the
+"""Small-batch models whose last two layers are fully connected: outside TIMED mode the last
+layer (no step) runs inside the launch of the layer before it (the batch <= 8 kernel or the
+32 x 32 tile kernel), as integer atomic additions into logits that the first layer's launch has
+zeroed.  Logits and every layer's outputs against the
 oracle, for widths that are not whole words, for the largest (batch x classes) that takes this
 path and the first that does not, on repeated runs over logits holding garbage, as graph replays
 and through the entry point that allocates nothing; TIMED mode (separate launches) must agree."""
@@ -61,8 +62,19 @@ def check(layers, in_shape, batch, cid, what):
     ((96, 1000, 65), 32, 7),          # 455 pairs
     ((512, 2050, 2), 784, 5),         # last word of the hidden layer holds two bits
     ((128, 4097, 1), 64, 8),          # a single logit; hidden width one bit over a word multiple
+    ((64, 8192, 10), 16, 2),          # the widest hidden layer that takes this path
+    ((64, 8224, 10), 16, 2),          # one word wider: separate launches
     ((256, 33, 10), 128, 2),          # hidden layer of two words, the second with one bit
     ((64, 96, 40, 10), 16, 4),        # two hidden FC layers before the last
+    # more than 8 rows: the 32 x 32 tile kernel
+    ((96, 1000, 16), 32, 40),         # 16 classes: the most it takes; two row blocks, the second ragged
+    ((96, 1000, 17), 32, 40),         # 17 classes: separate launches
+    ((100, 70, 9), 48, 33),           # ragged everywhere, one row in the second row block
+    ((512, 994, 2), 784, 100),        # last word of the hidden layer holds two bits
+    ((96, 1024, 10), 32, 70),         # the widest hidden layer that takes this path at more than 8 rows
+    ((96, 1056, 10), 32, 70),         # one word wider: separate launches
+    ((64, 33, 1), 16, 9),             # a single logit
+    ((64, 96, 40, 10), 16, 300),      # ten row blocks
 ])
 def test_fc_tail_shapes(widths, in_c, batch):
     require_gpu()
@@ -88,6 +100,13 @@ def test_fc_tail_after_each_first_layer_kernel(kh, pad, hw, c_in):
     layers = W.build_model([W.Layer(FIRST, c_in, 32, kh, kh, pad), W.Layer(FC, hw * hw * 32, 100),
                             W.Layer(FC, 100, 10, step=False)], hw, hw, c_in, cid)
     check(layers, (hw, hw, c_in), 3, cid, f"conv {kh}x{kh} on {hw}x{hw}x{c_in} -> 100 -> 10")
+
+
+@pytest.mark.parametrize("name,batch", [("mlp", 64), ("mlp", 300), ("small_cnn", 40), ("vgg_small", 20)])
+def test_fc_tail_benchmark_models_larger_batches(name, batch):
+    require_gpu()
+    cid, layers, in_shape = W.model_by_name(name)
+    check(layers, in_shape, batch, cid, name)
 
 
 def test_two_layer_model_has_no_tail_to_fold():
