@@ -67,3 +67,27 @@ def test_conv_sweep_three_runs_identical(hw, c):
         torch.cuda.synchronize()
         outs.append(o)
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+@pytest.mark.parametrize("name,batch", [("small_cnn", 5), ("vgg_small", 32), ("vgg_small", 256)])
+def test_two_model_objects_on_two_streams_at_once(name, batch):
+    """Independent batches issued alternately on two streams (each model object owns its workspace
+    and logits) overlap on the device; both must give what one stream alone gives, every time."""
+    import oracle
+    print("two streams", name, batch, flush=True)
+    cid, layers, in_shape = W.model_by_name(name)
+    imgs_a = W.draw_images(W.rng_for(cid, 0, 0), batch, *in_shape)
+    imgs_b = W.draw_images(W.rng_for(cid, 0, 1), batch, *in_shape)
+    want = [oracle.run_model(layers, im)[0] for im in (imgs_a, imgs_b)]
+    dms = [DeviceModel(layers, batch, in_shape) for _ in range(2)]
+    xs = [dev(imgs_a), dev(imgs_b)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(6):
+        for i in range(2):
+            with torch.cuda.stream(streams[i]):
+                dms[i].logits.fill_(-9)
+                dms[i].run(xs[i], P.RUN_STREAM)
+        torch.cuda.synchronize()
+        for i in range(2):
+            np.testing.assert_array_equal(dms[i].logits.cpu().numpy(), want[i], err_msg=f"stream {i}, repeat {rep}")
