@@ -31,12 +31,6 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // launches are latency-bound), the 256 x 256 tile short ones (registers).
 constexpr int chunk_words(int tm, int tn) { return tm * tn >= 16 ? 16 : (tm * tn >= 4 ? 32 : 64); }
 
-// (experiments may override the start stagger at build time)
-#ifdef BNN_GEMM_TUNE
-static unsigned gemm_stagger_ticks(unsigned dflt) { const char *e = getenv("GEMM_STAGGER_US"); return e ? (unsigned)(atof(e) * 100) : dflt; }
-#else
-static unsigned gemm_stagger_ticks(unsigned dflt) { return dflt; }
-#endif
 
 template <int VEC>
 __device__ __forceinline__ uint4 load_row_words(const uint32_t *__restrict__ base, int64_t row,
@@ -596,7 +590,7 @@ bnn_status launch_mfma(const uint32_t *a, int64_t m, int64_t k, const uint32_t *
     if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
     gw.nbm = (int)nbm; gw.nbn = (int)nbn;
     // two or more rounds of the 256 x 256 tile: the first round starts spread over 10 us
-    gw.stagger_ticks = (TM * TN >= 16 && blocks >= 512) ? gemm_stagger_ticks(1000) : 0;
+    gw.stagger_ticks = (TM * TN >= 16 && blocks >= 512) ? 1000 : 0;
     dim3 grid((unsigned)blocks);
     if ((kw & 3) == 0)
         hipLaunchKernelGGL((bgemm_mfma<TM, TN, 4>), grid, dim3(256), 0, s, a, b, m, n, kw, (int)k, gw, ep);
