@@ -17,7 +17,9 @@
 //                      operands straight from global memory.
 //   bgemv_rows         m <= 8: bandwidth-bound, xor + popcount on the VALU, four output rows of
 //                      B per wave, halving-butterfly reduction over the 64 lanes.
-// Both end in the same epilogue: optional int32 store, optional threshold/flip/bit-pack.
+// All end in the same epilogue: optional int32 store, optional threshold/flip/bit-pack.  The two
+// small-problem kernels can also carry the model's last layer (TAIL): each block adds the share
+// of its 32-bit output words to the logits.
 #include "bnn_internal.h"
 
 namespace bnn {
