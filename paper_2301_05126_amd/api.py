@@ -103,10 +103,16 @@ def _ptr(x):
     return x.data_ptr()
 
 
+_torch = None
+
+
 def _stream(stream):
     if stream is None:
-        import torch
-        return torch.cuda.current_stream().cuda_stream
+        global _torch
+        if _torch is None:
+            import torch
+            _torch = torch
+        return _torch.cuda.current_stream().cuda_stream
     if isinstance(stream, int):
         return stream
     return stream.cuda_stream
@@ -178,11 +184,14 @@ def bnn_model_workspace_bytes(model):
     return int(_lib.bnn_model_workspace_bytes(model.handle))
 
 
+_NO_HOST_FN = HOST_LAYER_FN(0)
+
+
 def bnn_run_model(model, input_dev, logits_dev, workspace_dev, workspace_bytes, mode=RUN_STREAM,
                   host_fn=None, stream=None):
     """Returns the list of LayerTiming in TIMED mode, else None."""
     timings = (LayerTiming * model.n_layers)() if mode == RUN_TIMED else None
-    cb = HOST_LAYER_FN(lambda layer, ctx: host_fn(layer)) if host_fn else HOST_LAYER_FN(0)
+    cb = HOST_LAYER_FN(lambda layer, ctx: host_fn(layer)) if host_fn else _NO_HOST_FN
     _check(_lib.bnn_run_model(model.handle, _ptr(input_dev), _ptr(logits_dev), _ptr(workspace_dev),
                               workspace_bytes, mode, timings, cb, None, _stream(stream)),
            "bnn_run_model")

@@ -796,6 +796,192 @@ __global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// A few thousand output pixels at most (batch 1 .. 8 of a small image): latency is what counts.
+// One wave = 32 output pixels x 32 output channels and nothing is staged: a lane half owns one
+// kernel row (ti = 2 * K step + half; kernel height <= 4, a row's kw * c_in <= 16 bytes), reads
+// the row's bytes of its pixel and of its channel's weights as five dwords around the unaligned
+// start (buffer loads: dwords outside the tensor read as zero) and shifts them into place; bytes
+// left or right of the image, and rows above or below it, become the pad value.  Two
+// v_mfma_i32_32x32x32_i8 (rows = channels, columns = pixels), then the step in registers: a lane
+// holds 16 of its pixel's 32 channel bits, the other half of the wave the rest; with pooling the
+// four lanes of a 2x2 window (pixels are window-major then) combine their words or their sums.
+struct FirstGeomS {
+    int n, h, w, c_in, c_out, kh, kw, sl, pad, pad_value;
+    int ho, wo, pool, npix;
+    int w2, hw2;                 // output columns and pixels per image, in windows when pooling
+    unsigned mg_w2, mg_hw2;
+};
+
+__device__ __forceinline__ unsigned bytes_below(int t)      // mask of the bytes b < t of a dword
+{
+    return t <= 0 ? 0u : (t >= 4 ? 0xffffffffu : (1u << (8 * t)) - 1u);
+}
+
+__global__ __launch_bounds__(64) void conv_first_small(const int8_t *__restrict__ in, const int8_t *__restrict__ wt,
+                                                       FirstGeomS g, EpiArgs ep, ClearArgs clr)
+{
+    if (clr.count > 0 && blockIdx.y == 0)
+        for (int i = blockIdx.x * 64 + threadIdx.x; i < clr.count; i += gridDim.x * 64) clr.ptr[i] = 0;
+
+    const int lane = threadIdx.x;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int o0 = blockIdx.y * 32;
+    const int oc = o0 + l32;                                  // this lane's weight row
+
+    // this lane's pixel
+    const int p = blockIdx.x * 32 + l32;
+    const bool pix_ok = p < g.npix;
+    const int q = g.pool == 2 ? p >> 2 : p, sub = g.pool == 2 ? p & 3 : 0;
+    const int img = div_by(q, g.hw2, g.mg_hw2);
+    const int rem = q - img * g.hw2;
+    const int wy = div_by(rem, g.w2, g.mg_w2), wx = rem - wy * g.w2;
+    const int y = wy * g.pool + (sub >> 1), x = wx * g.pool + (sub & 1);
+
+    // thresholds and flips of this lane's 16 channels (register r: channel 8 (r / 4) + 4 half + r % 4
+    // of the tile), on their way early: one address per lane plus immediate offsets; channels
+    // past c_out read as zero and are masked off at the end
+    int thr[16];
+    unsigned flp[16];
+    const bool has_flip = ep.packed && ep.flip;
+    if (ep.packed) {
+        const __amdgpu_buffer_rsrc_t tr =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(ep.thr), 0, g.c_out * 4, 0x00020000);
+        const int tb = (o0 + half * 4) * 4;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            thr[r] = __builtin_amdgcn_raw_buffer_load_b32(tr, tb + ((r >> 2) * 8 + (r & 3)) * 4, 0, 0);
+        if (has_flip) {
+            const __amdgpu_buffer_rsrc_t fr =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(ep.flip), 0, g.c_out, 0x00020000);
+            const int fb = o0 + half * 4;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                flp[r] = __builtin_amdgcn_raw_buffer_load_b8(fr, fb + (r >> 2) * 8 + (r & 3), 0, 0);
+        }
+    }
+
+    const __amdgpu_buffer_rsrc_t ir = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(in), 0, (g.n * g.h * g.w * g.c_in + 3) & ~3, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(wt), 0, (g.c_out * g.kh * g.sl + 3) & ~3, 0x00020000);
+
+    unsigned xa[2][5], xw[2][5];
+    int a_addr[2], w_addr[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int ti = 2 * ks + half;
+        a_addr[ks] = ((img * g.h + (y + ti - g.pad)) * g.w + (x - g.pad)) * g.c_in;
+        w_addr[ks] = (oc * g.kh + ti) * g.sl;
+#pragma unroll
+        for (int d = 0; d < 5; ++d) {
+            // (a dword that starts below zero holds no image byte; its offset becomes one past every
+            // tensor this kernel accepts, which reads as zero.  Weight offsets are never negative.)
+            const unsigned ao = min((unsigned)((a_addr[ks] & ~3) + 4 * d), 0x7ffffff0u);
+            xa[ks][d] = __builtin_amdgcn_raw_buffer_load_b32(ir, (int)ao, 0, 0);
+            xw[ks][d] = __builtin_amdgcn_raw_buffer_load_b32(wr, (w_addr[ks] & ~3) + 4 * d, 0, 0);
+        }
+    }
+
+    // bytes of a kernel row that lie left of the image (columns x - pad + tj < 0) or right of it
+    const int lo = (g.pad - x > 0 ? g.pad - x : 0) * g.c_in;
+    const int right = g.w + g.pad - x;
+    const int hi = (right < g.kw ? (right > 0 ? right : 0) : g.kw) * g.c_in;
+    const unsigned padv4 = (unsigned)(uint8_t)(int8_t)g.pad_value * 0x01010101u;
+    unsigned outside[4], wkeep[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        outside[d] = bytes_below(lo - 4 * d) | ~bytes_below(hi - 4 * d);
+        wkeep[d] = bytes_below(g.sl - 4 * d);                 // a weight row's own bytes; K padding is zero
+    }
+
+    v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int ti = 2 * ks + half;
+        const int yy = y + ti - g.pad;
+        const bool row_in = pix_ok && yy >= 0 && yy < g.h;
+        const bool w_ok = ti < g.kh && oc < g.c_out;
+        const unsigned sa = (unsigned)a_addr[ks] & 3u, swt = (unsigned)w_addr[ks] & 3u;
+        v4i av, wv;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const unsigned ad = __builtin_amdgcn_alignbyte(xa[ks][d + 1], xa[ks][d], sa);
+            const unsigned wd = __builtin_amdgcn_alignbyte(xw[ks][d + 1], xw[ks][d], swt);
+            av[d] = (int)(row_in ? ((ad & ~outside[d]) | (padv4 & outside[d])) : padv4);
+            wv[d] = (int)(w_ok ? wd & wkeep[d] : 0u);
+        }
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, av, acc, 0, 0, 0);
+    }
+
+    if (ep.preact && pix_ok) {
+        int32_t *dst = ep.preact + ((int64_t)(img * g.ho + y) * g.wo + x) * g.c_out;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int o = o0 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (o < g.c_out) dst[o] = acc[r];
+        }
+    }
+    if (ep.packed) {
+        if (g.pool == 2 && ep.pool_first != 0) {    // max over the window's four lanes, then the step
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int v = acc[r];
+                v = max(v, __shfl_xor(v, 1));
+                acc[r] = max(v, __shfl_xor(v, 2));
+            }
+        }
+        // decision of register r in bit r: the sign of thr - x, shifted in from the right
+        unsigned dec = 0, fl = 0;
+#pragma unroll
+        for (int r = 15; r >= 0; --r) {
+            const int64_t diff = (int64_t)thr[r] - (int64_t)acc[r];          // negative iff x > thr
+            dec = (dec << 1) | (unsigned)((uint64_t)diff >> 63);
+        }
+        if (has_flip) {
+#pragma unroll
+            for (int r = 15; r >= 0; --r) fl = (fl << 1) | (flp[r] != 0 ? 1u : 0u);
+        }
+        dec ^= fl;
+        // nibble r / 4 of the 16 bits goes to bits 8 (r / 4) + 4 half .. + 3 of the channel word
+        unsigned bits = (dec & 0x000fu) | ((dec & 0x00f0u) << 4) | ((dec & 0x0f00u) << 8) | ((dec & 0xf000u) << 12);
+        bits <<= 4 * half;
+        unsigned word = bits | (unsigned)__shfl_xor((int)bits, 32);
+        const int left = g.c_out - o0;              // channels of this tile that exist
+        word &= left >= 32 ? 0xffffffffu : (1u << left) - 1u;
+        if (g.pool == 2 && ep.pool_first == 0) {    // max of +-1 values = OR of the bits
+            word |= (unsigned)__shfl_xor((int)word, 1);
+            word |= (unsigned)__shfl_xor((int)word, 2);
+        }
+        const int nw = (g.c_out + 31) >> 5;
+        if (half == 0 && pix_ok && sub == 0) ep.packed[(int64_t)q * nw + blockIdx.y] = word;
+    }
+}
+
+bnn_status launch_first_small(const int8_t *in, const int8_t *wt, int n, int h, int w, int c_in, int c_out,
+                              int kh, int kw, int pad, int pad_value, const EpiArgs &ep, const ClearArgs &clr,
+                              hipStream_t s)
+{
+    FirstGeomS g;
+    g.n = n; g.h = h; g.w = w; g.c_in = c_in; g.c_out = c_out; g.kh = kh; g.kw = kw; g.sl = kw * c_in;
+    g.pad = pad; g.pad_value = pad_value;
+    g.ho = h + 2 * pad - kh + 1; g.wo = w + 2 * pad - kw + 1;
+    g.pool = ep.packed ? ep.pool : 1;
+    const int64_t npix = (int64_t)n * g.ho * g.wo;
+    if (kh > 4 || g.sl > 16 || npix > 8192 || (int64_t)n * h * w * c_in > 0x7ffffff0LL ||
+        (int64_t)c_out * kh * g.sl > 0x7ffffff0LL || c_out > 65535 * 32)
+        return BNN_ERR_UNSUPPORTED;
+    g.npix = (int)npix;
+    g.w2 = g.wo / g.pool;
+    g.hw2 = (g.ho / g.pool) * g.w2;
+    g.mg_w2 = magic_floor(g.w2); g.mg_hw2 = magic_floor(g.hw2);
+    const dim3 grid((unsigned)((npix + 31) / 32), (unsigned)((c_out + 31) / 32));
+    hipLaunchKernelGGL(conv_first_small, grid, dim3(64), 0, s, in, wt, g, ep, clr);
+    return hip_result(hipGetLastError());
+}
+
 template <int NG>
 bnn_status launch_first_mfma(const int8_t *in, const int8_t *wt, FirstGeomM &g, const EpiArgs &ep,
                              const ClearArgs &clr, hipStream_t s)
@@ -903,6 +1089,11 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
             hipLaunchKernelGGL(fc_first_mfma, dim3((unsigned)blocks), dim3(256), 0, s, in, wt, M, c_out, c_in, ep, clr);
             return hip_result(hipGetLastError());
         }
+    }
+    // a few thousand pixels: one wave per 32 x 32 outputs, nothing staged
+    {
+        const bnn_status st = launch_first_small(in, wt, n, h, w, c_in, c_out, kh, kw, pad, pad_value, ep, clr, s);
+        if (st != BNN_ERR_UNSUPPORTED) return st;
     }
     // 3x3 over small images: whole images in LDS
     if (kh == 3 && kw == 3 && pad == 1 && c_in <= 4 && (int64_t)n * h * w * c_in < 0x7fffffff00LL) {
