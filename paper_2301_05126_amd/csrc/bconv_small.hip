@@ -5,7 +5,9 @@
 // of K = one channel word per lane half of one tap; a unit = consecutive words of one tap, one
 // vector load per operand): wave v takes the units v, v + 4, ..., reads its operand words straight
 // from global memory (all loads in flight together with the thresholds and flips, no staging),
-// and the partial sums meet in LDS.  (Eight waves per block were measured and are not faster.)  Wave 0 then runs the same step / pool / pack epilogue as the tile kernels.
+// and the partial sums meet in LDS.  (Eight waves per block were measured and are not faster.)  Wave 0
+// then runs the step, the pooling and the packing in its registers (a batch-1 launch is bound by its
+// instruction count: the tile kernels' epilogue through LDS is three times as long).
 // Same conventions: pixels in window-major order, weights as the MFMA's first matrix (rows =
 // channels, lanes = pixels), out-of-image taps = -1 = zero bits, FP4 +-1 operands.
 #include "bnn_internal.h"
@@ -31,7 +33,6 @@ __global__ __launch_bounds__(256) void bconv_small(const uint32_t *__restrict__ 
 {
     constexpr int NW = 4;                // waves of the block
     __shared__ float red[NW - 1][16][64];    // partial sums of waves 1..NW-1
-    __shared__ uint32_t outw[32];        // the tile's packed words, one per output pixel
     constexpr int UW = WPH < 4 ? WPH : 4;    // words (= steps) per unit
     constexpr int UPT = WPH / UW;            // units per tap
     constexpr int NU = 9 * UPT;              // units of the whole K
@@ -88,16 +89,17 @@ __global__ __launch_bounds__(256) void bconv_small(const uint32_t *__restrict__ 
         }
     }
 
-    // wave 0's epilogue parameters, requested now so that they arrive with the operands
+    // wave 0's epilogue parameters, requested now so that they arrive with the operands: the
+    // thresholds of the lane's 16 channels, and the flip of channel o0 + l32 (one per lane)
     int th[16];
-    StepWords<1> sw;
+    unsigned flipv = 0;
     if (wave == 0 && ep.packed) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int c = o0 + (r >> 2) * 8 + half * 4 + (r & 3);
             th[r] = ep.thr[c < g.c_out ? c : 0];
         }
-        sw = load_step_words<1>(ep, o0, l32, g.c_out);
+        if (ep.flip) flipv = ep.flip[ch_ok ? o : 0];
     }
 
     uint32_t sgn = 0x88888888u, one = 0x22222222u;
@@ -134,21 +136,40 @@ __global__ __launch_bounds__(256) void bconv_small(const uint32_t *__restrict__ 
             conv_tile_store_preact<1, 1>(getx, 0, o0, l32, half, pos, ep.preact);
         }
         if (ep.packed) {
-            // x - T - 1/2: never zero, negative exactly when x <= T (T clamped to +-(K + 1))
-            const int bound = g.k_bits + 1;
+            // The step in registers: register r of lane (l32, half) is channel 8 (r / 4) + 4 half + r % 4
+            // of pixel l32; the four lanes 4 j .. 4 j + 3 are one 2x2 window (window-major pixels).
+            const bool pool2 = ep.pool == 2, pool_first = pool2 && ep.pool_first != 0;
+            int xv[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int tc = th[r] > bound ? bound : (th[r] < -bound ? -bound : th[r]);
-                acc[r] -= (float)tc + 0.5f;
+            for (int r = 0; r < 16; ++r) xv[r] = (int)acc[r];
+            if (pool_first) {                       // max over the window, then the step
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int v = max(xv[r], __shfl_xor(xv[r], 1));
+                    xv[r] = max(v, __shfl_xor(v, 2));
+                }
             }
-            auto gets = [&](int, int, int r) { return acc[r]; };
-            conv_tile_step_to_lds<1, 1>(gets, 0, 0, 1, l32, half, sw, ep.pool, ep.pool_first != 0, outw);
+            unsigned dec = 0;                       // bit r: x > T, the sign of T - x shifted in from the right
+#pragma unroll
+            for (int r = 15; r >= 0; --r) {
+                const int64_t diff = (int64_t)th[r] - (int64_t)xv[r];
+                dec = (dec << 1) | (unsigned)((uint64_t)diff >> 63);
+            }
+            unsigned bits = (dec & 0x000fu) | ((dec & 0x00f0u) << 4) | ((dec & 0x0f00u) << 8) | ((dec & 0xf000u) << 12);
+            bits <<= 4 * half;
+            unsigned word = bits | (unsigned)__shfl_xor((int)bits, 32);
+            word ^= (unsigned)__ballot(flipv != 0);             // both wave halves hold the tile's 32 flips
+            const int left = g.c_out - o0;
+            word &= left >= 32 ? 0xffffffffu : (1u << left) - 1u;
+            if (pool2 && !pool_first) {             // max of +-1 values = OR of the bits
+                word |= (unsigned)__shfl_xor((int)word, 1);
+                word |= (unsigned)__shfl_xor((int)word, 2);
+            }
+            const int nw = (g.c_out + 31) >> 5;
+            const int sh = pool2 ? 1 : 0;
+            const int64_t at = ((int64_t)(img * (g.h >> sh) + (y >> sh)) * (g.w >> sh) + (x >> sh)) * nw + (o0 >> 5);
+            if (half == 0 && pix_ok && (!pool2 || (l32 & 3) == 0)) ep.packed[at] = word;
         }
-    }
-    if (ep.packed) {
-        __syncthreads();
-        const CopyLane cl = make_copy_lane(32, pos, ep.pool, t);
-        conv_tile_copy_out<1>(outw, cl, o0 >> 5, pos, ep);
     }
 }
 

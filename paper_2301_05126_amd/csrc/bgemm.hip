@@ -624,6 +624,29 @@ bnn_status launch_small(const uint32_t *a, int64_t m, int64_t k, const uint32_t 
     return hip_result(hipGetLastError());
 }
 
+// m <= 8 rows; the kernel is instantiated for 1, 2, 4 and 8 rows (a batch-1 launch is bound by its
+// own instruction count, and the 8-row code is four times as long).
+template <bool TAIL>
+bnn_status launch_gemv(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n, int kw,
+                       const EpiArgs &ep, const FcTailArgs &tail, hipStream_t s)
+{
+    const dim3 grid((unsigned)ceil_div64(n, 32));
+    const bool v4 = (kw & 3) == 0;
+#define BNN_GEMV(MT)                                                                                          \
+    do {                                                                                                      \
+        if (v4)                                                                                               \
+            hipLaunchKernelGGL((bgemv_rows<MT, 4, TAIL>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, tail); \
+        else                                                                                                  \
+            hipLaunchKernelGGL((bgemv_rows<MT, 1, TAIL>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, tail); \
+    } while (0)
+    if (m == 1) BNN_GEMV(1);
+    else if (m == 2) BNN_GEMV(2);
+    else if (m <= 4) BNN_GEMV(4);
+    else BNN_GEMV(8);
+#undef BNN_GEMV
+    return hip_result(hipGetLastError());
+}
+
 }  // namespace
 
 bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint32_t *b, int64_t n,
@@ -632,13 +655,8 @@ bnn_status launch_fc_binary(const uint32_t *a, int64_t m, int64_t k, const uint3
     if (m == 0) return BNN_OK;
     const int kw = (int)((k + 31) / 32);
     if (m <= 8) {
-        dim3 grid((unsigned)ceil_div64(n, 32));
         const FcTailArgs none = {nullptr, nullptr, 0};
-        if ((kw & 3) == 0)
-            hipLaunchKernelGGL((bgemv_rows<8, 4, false>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, none);
-        else
-            hipLaunchKernelGGL((bgemv_rows<8, 1, false>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, none);
-        return hip_result(hipGetLastError());
+        return launch_gemv<false>(a, m, k, b, n, kw, ep, none, s);
     }
     // largest tile that still fills most of the 256 compute units
     const int64_t want = 192;
@@ -670,12 +688,7 @@ bnn_status launch_fc_binary_tail(const uint32_t *a, int64_t m, int64_t k, const 
         return BNN_ERR_UNSUPPORTED;
     const int kw = (int)((k + 31) / 32);
     if (m > 8) return launch_small<true>(a, m, k, b, n, kw, ep, tail, s);
-    dim3 grid((unsigned)ceil_div64(n, 32));
-    if ((kw & 3) == 0)
-        hipLaunchKernelGGL((bgemv_rows<8, 4, true>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, tail);
-    else
-        hipLaunchKernelGGL((bgemv_rows<8, 1, true>), grid, dim3(512), 0, s, a, b, (int)m, n, kw, (int)k, ep, tail);
-    return hip_result(hipGetLastError());
+    return launch_gemv<true>(a, m, k, b, n, kw, ep, tail, s);
 }
 
 }  // namespace bnn

@@ -840,10 +840,9 @@ __global__ __launch_bounds__(64) void conv_first_small(const int8_t *__restrict_
 
     // thresholds and flips of this lane's 16 channels (register r: channel 8 (r / 4) + 4 half + r % 4
     // of the tile), on their way early: one address per lane plus immediate offsets; channels
-    // past c_out read as zero and are masked off at the end
+    // past c_out read as zero and are masked off at the end (the clamped flip of such a lane too)
     int thr[16];
-    unsigned flp[16];
-    const bool has_flip = ep.packed && ep.flip;
+    unsigned flipv = 0;                     // flip of channel o0 + l32: one per lane
     if (ep.packed) {
         const __amdgpu_buffer_rsrc_t tr =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(ep.thr), 0, g.c_out * 4, 0x00020000);
@@ -851,14 +850,7 @@ __global__ __launch_bounds__(64) void conv_first_small(const int8_t *__restrict_
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             thr[r] = __builtin_amdgcn_raw_buffer_load_b32(tr, tb + ((r >> 2) * 8 + (r & 3)) * 4, 0, 0);
-        if (has_flip) {
-            const __amdgpu_buffer_rsrc_t fr =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(ep.flip), 0, g.c_out, 0x00020000);
-            const int fb = o0 + half * 4;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                flp[r] = __builtin_amdgcn_raw_buffer_load_b8(fr, fb + (r >> 2) * 8 + (r & 3), 0, 0);
-        }
+        if (ep.flip) flipv = ep.flip[oc < g.c_out ? oc : g.c_out - 1];
     }
 
     const __amdgpu_buffer_rsrc_t ir = __builtin_amdgcn_make_buffer_rsrc(
@@ -934,21 +926,17 @@ __global__ __launch_bounds__(64) void conv_first_small(const int8_t *__restrict_
             }
         }
         // decision of register r in bit r: the sign of thr - x, shifted in from the right
-        unsigned dec = 0, fl = 0;
+        unsigned dec = 0;
 #pragma unroll
         for (int r = 15; r >= 0; --r) {
             const int64_t diff = (int64_t)thr[r] - (int64_t)acc[r];          // negative iff x > thr
             dec = (dec << 1) | (unsigned)((uint64_t)diff >> 63);
         }
-        if (has_flip) {
-#pragma unroll
-            for (int r = 15; r >= 0; --r) fl = (fl << 1) | (flp[r] != 0 ? 1u : 0u);
-        }
-        dec ^= fl;
         // nibble r / 4 of the 16 bits goes to bits 8 (r / 4) + 4 half .. + 3 of the channel word
         unsigned bits = (dec & 0x000fu) | ((dec & 0x00f0u) << 4) | ((dec & 0x0f00u) << 8) | ((dec & 0xf000u) << 12);
         bits <<= 4 * half;
         unsigned word = bits | (unsigned)__shfl_xor((int)bits, 32);
+        word ^= (unsigned)__ballot(flipv != 0);     // both wave halves hold the tile's 32 flips
         const int left = g.c_out - o0;              // channels of this tile that exist
         word &= left >= 32 ? 0xffffffffu : (1u << left) - 1u;
         if (g.pool == 2 && ep.pool_first == 0) {    // max of +-1 values = OR of the bits
