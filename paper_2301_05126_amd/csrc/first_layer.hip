@@ -4,7 +4,12 @@
 // (paper Sec. II-A convolutional layer applied to the 8-bit input image; with
 // kh = kw = h = w = 1 it is the fully-connected first layer of an MLP).
 //
-// Three kernels, picked by shape:
+// Five kernels, picked by shape:
+//   conv_first_small  at most 8192 output pixels, kernel height <= 4, kernel rows of <= 16 bytes:
+//                     one wave per 32 pixels x 32 channels, operands straight from global
+//                     memory, the step in registers (latency: batch 1 .. 8 of a small image).
+//   conv_first_img    3x3, one ring of padding, <= 4 channels, power-of-two width: whole images
+//                     in LDS, persistent blocks (throughput: large batches of small images).
 //   conv_first_mfma   small kernels (kh * roundup16(kw*c_in) <= 128 bytes per pixel): the int8
 //                     input patch and the block's weights live in LDS; each lane gathers 16
 //                     contiguous patch bytes (one kernel row of one pixel) per MFMA operand
