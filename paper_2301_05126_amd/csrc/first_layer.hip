@@ -5,7 +5,7 @@
 // kh = kw = h = w = 1 it is the fully-connected first layer of an MLP).
 //
 // Five kernels, picked by shape:
-//   conv_first_small  at most 8192 output pixels, kernel height <= 4, kernel rows of <= 16 bytes:
+//   conv_first_small  at most 6144 tiles of 32 pixels x 32 channels, kernel height <= 4, kernel rows of <= 16 bytes:
 //                     one wave per 32 pixels x 32 channels, operands straight from global
 //                     memory, the step in registers (latency: batch 1 .. 8 of a small image).
 //   conv_first_img    3x3, one ring of padding, <= 4 channels, power-of-two width: whole images
@@ -802,7 +802,7 @@ __global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
-// A few thousand output pixels at most (batch 1 .. 8 of a small image): latency is what counts.
+// A few thousand tiles of 32 pixels x 32 channels at most (small batches of a small image): latency is what counts.
 // One wave = 32 output pixels x 32 output channels and nothing is staged: a lane half owns one
 // kernel row (ti = 2 * K step + half; kernel height <= 4, a row's kw * c_in <= 16 bytes), reads
 // the row's bytes of its pixel and of its channel's weights as five dwords around the unaligned
@@ -963,8 +963,11 @@ bnn_status launch_first_small(const int8_t *in, const int8_t *wt, int n, int h, 
     g.ho = h + 2 * pad - kh + 1; g.wo = w + 2 * pad - kw + 1;
     g.pool = ep.packed ? ep.pool : 1;
     const int64_t npix = (int64_t)n * g.ho * g.wo;
-    if (kh > 4 || g.sl > 16 || npix > 8192 || (int64_t)n * h * w * c_in > 0x7ffffff0LL ||
-        (int64_t)c_out * kh * g.sl > 0x7ffffff0LL || c_out > 65535 * 32)
+    // up to 6144 waves (pixel tiles x channel tiles): measured against the staged kernels on the two
+    // benchmark models' first layers, it wins below that (batch 48 / 64) and ties there
+    const int64_t waves = ((npix + 31) / 32) * ((c_out + 31) / 32);
+    if (kh > 4 || g.sl > 16 || waves > 6144 || (int64_t)n * h * w * c_in > 0x7ffffff0LL ||
+        (int64_t)c_out * kh * g.sl > 0x7ffffff0LL)
         return BNN_ERR_UNSUPPORTED;
     g.npix = (int)npix;
     g.w2 = g.wo / g.pool;

@@ -229,20 +229,21 @@ FIRST_SHAPES = [(2, 28, 28, 1, 64, 3, 3, 1, -1, 2), (2, 32, 32, 3, 128, 3, 3, 1,
                 (1300, 16, 16, 3, 64, 3, 3, 1, -128, 2),
                 # weight tensor of 33 * 27 = 891 bytes (not a whole number of dwords), ragged channel tile
                 (6, 8, 8, 3, 33, 3, 3, 1, 5, 1),
-                # up to 8192 output pixels the one-wave kernel runs (most shapes above with few images);
-                # its own edges: padding wider than the image, 4x4 kernel with 16-byte rows, 1x1 with
-                # pooling, input and weight tensors that are not whole numbers of dwords, one pixel
+                # up to 6144 tiles of 32 pixels x 32 channels the one-wave kernel runs (most shapes above with
+                # few images); its own edges: padding wider than the image, 4x4 kernel with 16-byte rows, 1x1
+                # with pooling, input and weight tensors that are not whole numbers of dwords, one pixel
                 (1, 2, 2, 1, 8, 3, 3, 20, -1, 1), (2, 4, 4, 16, 40, 1, 1, 0, -1, 2),
                 (3, 5, 5, 1, 20, 3, 3, 1, -5, 1), (1, 1, 1, 3, 5, 1, 1, 0, -1, 1),
                 (8, 32, 32, 3, 128, 3, 3, 1, -1, 1), (8, 28, 28, 1, 64, 3, 3, 1, -1, 2),
-                (1, 3, 90, 2, 70, 2, 7, 3, 9, 2),
-                # the same layers with enough images (more than 8192 output pixels) for the staged kernels
-                (12, 28, 28, 1, 64, 3, 3, 1, -1, 2), (140, 8, 8, 3, 32, 3, 3, 1, 0, 2),
-                (250, 5, 7, 2, 40, 3, 3, 1, 7, 1), (2100, 2, 2, 5, 70, 3, 3, 1, -1, 2),
-                (130, 9, 9, 2, 96, 2, 2, 0, -1, 1), (40, 16, 16, 4, 130, 4, 4, 1, -1, 1),
-                (40, 16, 16, 4, 64, 3, 3, 1, 0, 2), (140, 8, 8, 1, 40, 3, 3, 1, -1, 1),
-                (5, 64, 32, 3, 96, 3, 3, 1, 3, 1), (600, 4, 4, 2, 16, 3, 3, 1, -1, 2),
-                (130, 8, 8, 3, 33, 3, 3, 1, 5, 1), (9, 32, 32, 3, 128, 3, 3, 1, -1, 1)]
+                (1, 3, 90, 2, 70, 2, 7, 3, 9, 2), (48, 32, 32, 3, 128, 3, 3, 1, -1, 1),
+                # the same layers with enough images (more than 6144 such tiles) for the staged kernels
+                (130, 28, 28, 1, 64, 3, 3, 1, -1, 2), (3100, 8, 8, 3, 32, 3, 3, 1, 0, 2),
+                (2900, 5, 7, 2, 40, 3, 3, 1, 7, 1), (16500, 2, 2, 5, 70, 3, 3, 1, -1, 2),
+                (1100, 9, 9, 2, 96, 2, 2, 0, -1, 1), (180, 16, 16, 4, 130, 4, 4, 1, -1, 1),
+                (400, 16, 16, 4, 64, 3, 3, 1, 0, 2), (1600, 8, 8, 1, 40, 3, 3, 1, -1, 1),
+                (34, 64, 32, 3, 96, 3, 3, 1, 3, 1), (12400, 4, 4, 2, 16, 3, 3, 1, -1, 2),
+                (1600, 8, 8, 3, 33, 3, 3, 1, 5, 1), (50, 32, 32, 3, 128, 3, 3, 1, -1, 1),
+                (3, 6, 6, 2, 16, 3, 3, 130, 3, 1), (9, 128, 128, 1, 32, 3, 3, 1, -1, 2)]
 
 
 @pytest.mark.parametrize("n,h,w,ci,co,kh,kw,pad,padv,pool", FIRST_SHAPES)
