@@ -34,6 +34,9 @@ PEAK_BMAC = CUS * SIMDS * LANES_PER_CLK * CLOCK_HZ * 32 / 2     # 629.1e12 binar
 # one +-1 x +-1 product per FP4 MAC (2 flop).
 PEAK_FP4_TFLOPS = 10100.0
 PEAK_FP4_BMAC = PEAK_FP4_TFLOPS * 1e12 / 2
+# Dense int8 MFMA peak (published): 5.0 POP/s = 2.5e15 MAC/s -- the matrix-core roofline the binary
+# GEMM would have with unpacked +-1 int8 operands; quoted beside the FP4 one, which is what it runs on.
+PEAK_INT8_MAC = 2.5e15
 HBM_PEAK_GBS = 8000.0
 
 WORKLOADS = {
@@ -164,6 +167,7 @@ def section_gemm(P, W, torch):
                       "T_bMAC_s": round(rate / 1e12, 2),
                       "frac_fp4_mfma_peak": round(rate / PEAK_FP4_BMAC, 4),
                       "x_of_valu_popcount_roofline": round(rate / PEAK_BMAC, 3),
+                      "frac_int8_mfma_peak": round(rate / PEAK_INT8_MAC, 4),
                       "algorithmic_GBs": round(alg_bytes / (ev * 1e-3) / 1e9, 1)})
         if host_issued is not None:
             sweep[-1]["host_issued_us"] = host_issued
