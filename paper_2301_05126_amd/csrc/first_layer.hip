@@ -16,7 +16,8 @@
 //                     and v_mfma_i32_32x32x32_i8 does the sums.  Pixels are window-major, the
 //                     epilogue is the one of the binary convolution.
 //   fc_first_mfma     1x1 kernels without padding and c_in % 16 == 0 (the MLP's first layer):
-//                     an int8 GEMM whose operands are read straight from global memory.
+//                     an int8 GEMM whose operands are read straight from global memory
+//                     (fc_first_small: the same with K split over a block's waves, for few rows).
 //   conv_first_kernel any other shape: one lane = one output pixel x 32 output channels with
 //                     v_dot4_i32_i8.
 //
@@ -801,6 +802,80 @@ __global__ __launch_bounds__(256) void fc_first_mfma(const int8_t *__restrict__ 
     }
 }
 
+// The same int8 GEMM when the 64 x 64 blocks above would leave most compute units idle (the MLP's
+// first layer at batch 64: eight of them, each walking K = 784 alone with one load round trip per
+// step): a block owns 32 x 32 outputs and its four waves split K, wave v taking the 32-byte steps
+// v, v + 4, ... in rounds of up to eight with all loads of a round in flight; the partial sums
+// (integers) meet in LDS and wave 0 runs the epilogue.
+__global__ __launch_bounds__(256) void fc_first_small(const int8_t *__restrict__ A, const int8_t *__restrict__ Wt,
+                                                      int64_t M, int N, int K, int nbn, EpiArgs ep, ClearArgs clr)
+{
+    clear_words(clr);
+    constexpr int UR = 8;
+    __shared__ int red[3][16][64];
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int64_t m0 = (int64_t)(blockIdx.x / nbn) * 32;
+    const int n0 = (blockIdx.x % nbn) * 32;
+    const int64_t arow = (m0 + l32 < M) ? m0 + l32 : M - 1;
+    const int brow = (n0 + l32 < N) ? n0 + l32 : N - 1;
+    const int8_t *ap = A + arow * K;
+    const int8_t *bp = Wt + (int64_t)brow * K;
+    v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
+    const int nsteps = (K + 31) / 32;
+    for (int s0 = wave; s0 < nsteps; s0 += 4 * UR) {
+        v4i a[UR], b[UR];
+#pragma unroll
+        for (int k = 0; k < UR; ++k) {
+            const int ks = s0 + 4 * k;
+            const bool ok = ks < nsteps && ks * 32 + half * 16 < K;   // K % 16 == 0: a slice is all in or all out
+            const int koff = ok ? ks * 32 + half * 16 : 0;           // (else the row's first slice, zeroed)
+            a[k] = *reinterpret_cast<const v4i *>(ap + koff);
+            b[k] = *reinterpret_cast<const v4i *>(bp + koff);
+            if (!ok) { a[k] = v4i{0, 0, 0, 0}; b[k] = v4i{0, 0, 0, 0}; }
+        }
+#pragma unroll
+        for (int k = 0; k < UR; ++k)
+            if (s0 + 4 * k < nsteps) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[k], b[k], acc, 0, 0, 0);
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[wave - 1][r][lane] = acc[r];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] += red[0][r][lane] + red[1][r][lane] + red[2][r][lane];
+
+    // register r of lane (l32, half): row m0 + 8 (r / 4) + 4 half + r % 4, column n0 + l32
+    const int col = n0 + l32;
+    const bool cok = col < N;
+    if (ep.preact) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + (r >> 2) * 8 + half * 4 + (r & 3);
+            if (row < M && cok) ep.preact[row * N + col] = acc[r];
+        }
+    }
+    if (ep.packed) {
+        const int nw = (N + 31) >> 5;
+        const int thr = cok ? ep.thr[col] : 0;
+        const bool flip = cok && ep.flip && ep.flip[col];
+        unsigned mine = 0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const unsigned long long mask = __ballot(cok && ((acc[r] > thr) != flip));
+            const unsigned word = half ? (unsigned)(mask >> 32) : (unsigned)mask;
+            if (l32 == r) mine = word;          // lane r of each half keeps the word of register r
+        }
+        const int64_t row = m0 + (l32 >> 2) * 8 + half * 4 + (l32 & 3);
+        if (l32 < 16 && row < M) ep.packed[row * nw + (n0 >> 5)] = mine;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // A few thousand tiles of 32 pixels x 32 channels at most (small batches of a small image): latency is what counts.
 // One wave = 32 output pixels x 32 output channels and nothing is staged: a lane half owns one
@@ -1081,6 +1156,12 @@ bnn_status launch_conv_first_int8(const int8_t *in, int n, int h, int w, int c_i
     if (kh == 1 && kw == 1 && pad == 0 && (c_in & 15) == 0 && pool_ == 1) {
         const int64_t M = (int64_t)n * h * w;
         const int64_t blocks = ceil_div64(M, 64) * ceil_div64(c_out, 64);
+        if (blocks < 192) {
+            const int nbn = (c_out + 31) / 32;
+            const unsigned grid = (unsigned)(ceil_div64(M, 32) * nbn);
+            hipLaunchKernelGGL(fc_first_small, dim3(grid), dim3(256), 0, s, in, wt, M, c_out, c_in, nbn, ep, clr);
+            return hip_result(hipGetLastError());
+        }
         if (blocks <= 0x7fffffffLL) {
             hipLaunchKernelGGL(fc_first_mfma, dim3((unsigned)blocks), dim3(256), 0, s, in, wt, M, c_out, c_in, ep, clr);
             return hip_result(hipGetLastError());

@@ -243,7 +243,12 @@ FIRST_SHAPES = [(2, 28, 28, 1, 64, 3, 3, 1, -1, 2), (2, 32, 32, 3, 128, 3, 3, 1,
                 (400, 16, 16, 4, 64, 3, 3, 1, 0, 2), (1600, 8, 8, 1, 40, 3, 3, 1, -1, 1),
                 (34, 64, 32, 3, 96, 3, 3, 1, 3, 1), (12400, 4, 4, 2, 16, 3, 3, 1, -1, 2),
                 (1600, 8, 8, 3, 33, 3, 3, 1, 5, 1), (50, 32, 32, 3, 128, 3, 3, 1, -1, 1),
-                (3, 6, 6, 2, 16, 3, 3, 130, 3, 1), (9, 128, 128, 1, 32, 3, 3, 1, -1, 2)]
+                (3, 6, 6, 2, 16, 3, 3, 130, 3, 1), (9, 128, 128, 1, 32, 3, 3, 1, -1, 2),
+                # 1x1 layers: below 192 blocks of 64 x 64 the K-split kernel runs (the shapes further up, and
+                # K over two rounds of eight steps per wave, ragged rows and channels); above, the plain one
+                (70, 1, 1, 1072, 96, 1, 1, 0, -1, 1), (33, 1, 1, 784, 100, 1, 1, 0, -1, 1),
+                (12300, 1, 1, 16, 40, 1, 1, 0, -1, 1), (12300, 1, 1, 48, 33, 1, 1, 0, -1, 1),
+                (2000, 1, 1, 784, 512, 1, 1, 0, -1, 1)]
 
 
 @pytest.mark.parametrize("n,h,w,ci,co,kh,kw,pad,padv,pool", FIRST_SHAPES)
